@@ -1,0 +1,187 @@
+/*
+ * CPU oracle for the GPU embedding cache (level-1 store of the Hierarchical Parameter Server).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, single-threaded, obviously-correct
+ * statement of what the cache computes.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may load it; the product path never does.  It shares no code, header,
+ * table or constant generator with the HIP implementation.
+ *
+ * What it follows (paper sections / algorithms):
+ *   - Data model, Sec. 4.1: a slot holds a key and an embedding vector; a key is mapped by a
+ *     hash to exactly one set (the paper's "slabset") and may sit in any slot of that set.
+ *   - Query, Sec. 4.2 and Alg. 2: for each key, search its set; a hit copies the stored
+ *     vector to the result row of that key's index; a miss appends <index, key> to M.
+ *     The result row of a missing index is not written.
+ *   - Replace, Sec. 4.2 and Alg. 3: a key that is already cached is ignored; otherwise empty
+ *     slots are filled first and, when the set is full, a resident slot is overwritten.
+ *   - Update, Sec. 4.2 and Alg. 4: a cached key gets its vector overwritten; any other key is
+ *     ignored.
+ *   - Dump, Sec. 4.2: the keys currently cached.
+ *
+ * Readings where the paper is silent or differs from this build's contract:
+ *   - Geometry: a set has W slots (W a power of two, 1..64); the paper's 32-slot slabs and
+ *     the choice of the first slab to probe only permute the search order inside one set
+ *     and cannot change any result, so they do not appear here.
+ *   - Victim choice: the paper picks the least-recently-used slot from per-slot access
+ *     counters.  This build's contract replaces that by one counter per set:
+ *     way = C[s] mod W, then C[s] += 1.  Because nothing is ever deleted, that fills
+ *     ways 0..W-1 first ("empty slots first") and afterwards evicts in insertion order.
+ *     Query is therefore read-only.
+ *   - Hash: the paper names none.  set = (upper 32 bits of mix64(key)) mod S where mix64 is
+ *     the 64-bit finaliser of the splitmix64 generator.
+ *   - Empty marker: INT64_MIN ("Null" in Alg. 2-4).  INT64_MIN and INT64_MIN+1 are reserved:
+ *     query reports them as misses, insert and update skip them.
+ *   - Duplicates in a batch are handled by plain index order: every missing position gets
+ *     its own miss-list entry; the first occurrence of a new key inserts, later ones find it.
+ *   - Rows are opaque 32-bit patterns (no floating-point arithmetic anywhere).
+ *
+ * Every batch is processed sequentially in index order.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define HPSO_EMPTY    INT64_MIN
+#define HPSO_RESERVED (INT64_MIN + 1)
+
+typedef struct {
+    uint64_t S;      /* number of sets                        */
+    uint32_t W;      /* slots per set                         */
+    uint32_t d;      /* 32-bit words per row                  */
+    int64_t  *K;     /* [S][W]    keys, HPSO_EMPTY when free  */
+    uint32_t *V;     /* [S][W][d] rows as bit patterns        */
+    uint32_t *C;     /* [S]       per-set victim counter      */
+} hpso_t;
+
+/* Finaliser of splitmix64: three xor-shifts around two odd multipliers, all mod 2^64. */
+uint64_t hpso_mix64(uint64_t x)
+{
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ULL;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBULL;
+    x ^= x >> 31;
+    return x;
+}
+
+/* Alg. 2, "find slabset": hash of the key modulo the number of sets. */
+uint64_t hpso_set_of(const hpso_t *c, int64_t key)
+{
+    uint32_t h = (uint32_t)(hpso_mix64((uint64_t)key) >> 32);
+    return (uint64_t)h % c->S;
+}
+
+static int is_reserved(int64_t key)
+{
+    return key == HPSO_EMPTY || key == HPSO_RESERVED;
+}
+
+/* Search the key's set; returns the way holding it, or -1. */
+static int find_way(const hpso_t *c, uint64_t s, int64_t key)
+{
+    for (uint32_t w = 0; w < c->W; ++w)
+        if (c->K[s * c->W + w] == key)
+            return (int)w;
+    return -1;
+}
+
+hpso_t *hpso_create(uint64_t capacity, uint32_t W, uint32_t d)
+{
+    if (W == 0 || W > 64 || (W & (W - 1)) != 0 || d == 0 || capacity == 0 ||
+        capacity % W != 0 || capacity / W >= (1ULL << 31))
+        return NULL;
+    hpso_t *c = (hpso_t *)calloc(1, sizeof(hpso_t));
+    if (!c) return NULL;
+    c->S = capacity / W;
+    c->W = W;
+    c->d = d;
+    c->K = (int64_t *)malloc(sizeof(int64_t) * capacity);
+    c->V = (uint32_t *)calloc(capacity * (uint64_t)d, sizeof(uint32_t));
+    c->C = (uint32_t *)calloc(c->S, sizeof(uint32_t));
+    if (!c->K || !c->V || !c->C) {
+        free(c->K); free(c->V); free(c->C); free(c);
+        return NULL;
+    }
+    for (uint64_t i = 0; i < capacity; ++i) c->K[i] = HPSO_EMPTY;
+    return c;
+}
+
+void hpso_destroy(hpso_t *c)
+{
+    if (!c) return;
+    free(c->K); free(c->V); free(c->C); free(c);
+}
+
+uint64_t  hpso_num_sets(const hpso_t *c) { return c->S; }
+uint32_t  hpso_ways(const hpso_t *c)     { return c->W; }
+uint32_t  hpso_dim(const hpso_t *c)      { return c->d; }
+int64_t  *hpso_keys(hpso_t *c)           { return c->K; }
+uint32_t *hpso_vals(hpso_t *c)           { return c->V; }
+uint32_t *hpso_ctr(hpso_t *c)            { return c->C; }
+
+/*
+ * Query (Alg. 2).  out is [n][d]; rows of missing positions are left untouched.
+ * miss_idx / miss_keys receive <index, key> in ascending index order.  Returns |M|.
+ */
+uint64_t hpso_query(const hpso_t *c, const int64_t *keys, uint64_t n,
+                    uint32_t *out, uint32_t *miss_idx, int64_t *miss_keys)
+{
+    uint64_t n_miss = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        int64_t q = keys[i];
+        int w = -1;
+        uint64_t s = 0;
+        if (!is_reserved(q)) {
+            s = hpso_set_of(c, q);
+            w = find_way(c, s, q);
+        }
+        if (w < 0) {
+            miss_idx[n_miss] = (uint32_t)i;
+            miss_keys[n_miss] = q;
+            ++n_miss;
+        } else {
+            memcpy(out + i * c->d, c->V + (s * c->W + (uint64_t)w) * c->d,
+                   sizeof(uint32_t) * c->d);
+        }
+    }
+    return n_miss;
+}
+
+/* Replace (Alg. 3) with the per-set victim counter as the slot choice. */
+void hpso_insert(hpso_t *c, const int64_t *keys, const uint32_t *vals, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        int64_t q = keys[i];
+        if (is_reserved(q)) continue;
+        uint64_t s = hpso_set_of(c, q);
+        if (find_way(c, s, q) >= 0) continue;          /* already cached: ignored */
+        uint32_t w = c->C[s] % c->W;
+        c->C[s] += 1;                                   /* wraps mod 2^32; W divides 2^32 */
+        c->K[s * c->W + w] = q;
+        memcpy(c->V + (s * c->W + w) * c->d, vals + i * c->d, sizeof(uint32_t) * c->d);
+    }
+}
+
+/* Update (Alg. 4): overwrite the vector of keys that are cached, ignore the rest. */
+void hpso_update(hpso_t *c, const int64_t *keys, const uint32_t *vals, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        int64_t q = keys[i];
+        if (is_reserved(q)) continue;
+        uint64_t s = hpso_set_of(c, q);
+        int w = find_way(c, s, q);
+        if (w < 0) continue;
+        memcpy(c->V + (s * c->W + (uint64_t)w) * c->d, vals + i * c->d,
+               sizeof(uint32_t) * c->d);
+    }
+}
+
+/* Dump (Sec. 4.2): the cached keys, in slot order.  Returns how many were written. */
+uint64_t hpso_dump(const hpso_t *c, int64_t *keys_out)
+{
+    uint64_t m = 0;
+    for (uint64_t i = 0; i < c->S * c->W; ++i)
+        if (c->K[i] != HPSO_EMPTY)
+            keys_out[m++] = c->K[i];
+    return m;
+}

@@ -1,0 +1,150 @@
+"""ctypes front end of oracle/hps_oracle.c (test infrastructure only).
+
+All arithmetic of the method lives in the C file; this module only marshals numpy arrays.
+Rows are carried as uint32 bit patterns ([n, d] arrays); float32 arrays are reinterpreted,
+never converted.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+EMPTY_KEY = -(1 << 63)          # "Null" key of Alg. 2-4
+RESERVED_KEY = -(1 << 63) + 1   # second reserved value of the build's contract
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.build()
+    lib = C.CDLL(path)
+    vp, u64, u32 = C.c_void_p, C.c_uint64, C.c_uint32
+    lib.hpso_mix64.restype = u64
+    lib.hpso_mix64.argtypes = [u64]
+    lib.hpso_create.restype = vp
+    lib.hpso_create.argtypes = [u64, u32, u32]
+    lib.hpso_destroy.restype = None
+    lib.hpso_destroy.argtypes = [vp]
+    lib.hpso_set_of.restype = u64
+    lib.hpso_set_of.argtypes = [vp, C.c_int64]
+    lib.hpso_num_sets.restype = u64
+    lib.hpso_num_sets.argtypes = [vp]
+    for name in ("hpso_keys", "hpso_vals", "hpso_ctr"):
+        getattr(lib, name).restype = vp
+        getattr(lib, name).argtypes = [vp]
+    lib.hpso_query.restype = u64
+    lib.hpso_query.argtypes = [vp, vp, u64, vp, vp, vp]
+    lib.hpso_insert.restype = None
+    lib.hpso_insert.argtypes = [vp, vp, vp, u64]
+    lib.hpso_update.restype = None
+    lib.hpso_update.argtypes = [vp, vp, vp, u64]
+    lib.hpso_dump.restype = u64
+    lib.hpso_dump.argtypes = [vp, vp]
+    _lib = lib
+    return lib
+
+
+def mix64(x: int) -> int:
+    return int(_load().hpso_mix64(C.c_uint64(x & 0xFFFFFFFFFFFFFFFF)))
+
+
+def _keys(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a
+
+
+def _rows(a, n, d):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32:
+        a = a.view(np.uint32)
+    if a.dtype != np.uint32:
+        raise TypeError("rows must be float32 or uint32 bit patterns")
+    if a.shape != (n, d):
+        raise ValueError(f"rows must have shape {(n, d)}, got {a.shape}")
+    return a
+
+
+class OracleCache:
+    """One set-associative cache of `capacity` slots, `ways` slots per set, `dim` words per row."""
+
+    def __init__(self, capacity: int, ways: int, dim: int):
+        lib = _load()
+        self._lib = lib
+        self._h = lib.hpso_create(capacity, ways, dim)
+        if not self._h:
+            raise ValueError("invalid cache geometry")
+        self.S = int(lib.hpso_num_sets(self._h))
+        self.W = ways
+        self.d = dim
+        n = self.S * self.W
+        self.keys = np.ctypeslib.as_array(
+            C.cast(lib.hpso_keys(self._h), C.POINTER(C.c_int64)), shape=(self.S, self.W))
+        self.vals = np.ctypeslib.as_array(
+            C.cast(lib.hpso_vals(self._h), C.POINTER(C.c_uint32)), shape=(self.S, self.W, dim))
+        self.ctr = np.ctypeslib.as_array(
+            C.cast(lib.hpso_ctr(self._h), C.POINTER(C.c_uint32)), shape=(self.S,))
+        assert self.keys.size == n
+
+    def close(self):
+        if self._h:
+            self.keys = self.vals = self.ctr = None
+            self._lib.hpso_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_of(self, key: int) -> int:
+        return int(self._lib.hpso_set_of(self._h, C.c_int64(key)))
+
+    def query(self, keys, out=None):
+        """Returns (out, miss_idx, miss_keys).  `out` ([n, d] uint32) keeps its miss rows."""
+        keys = _keys(keys)
+        n = keys.shape[0]
+        if out is None:
+            out = np.zeros((n, self.d), dtype=np.uint32)
+        else:
+            assert out.dtype == np.uint32 and out.shape == (n, self.d) and out.flags.c_contiguous
+        mi = np.empty(max(n, 1), dtype=np.uint32)
+        mk = np.empty(max(n, 1), dtype=np.int64)
+        m = self._lib.hpso_query(self._h, keys.ctypes.data, n, out.ctypes.data,
+                                 mi.ctypes.data, mk.ctypes.data)
+        return out, mi[:m].copy(), mk[:m].copy()
+
+    def insert(self, keys, rows):
+        keys = _keys(keys)
+        rows = _rows(rows, keys.shape[0], self.d)
+        self._lib.hpso_insert(self._h, keys.ctypes.data, rows.ctypes.data, keys.shape[0])
+
+    def update(self, keys, rows):
+        keys = _keys(keys)
+        rows = _rows(rows, keys.shape[0], self.d)
+        self._lib.hpso_update(self._h, keys.ctypes.data, rows.ctypes.data, keys.shape[0])
+
+    def dump(self):
+        buf = np.empty(self.S * self.W, dtype=np.int64)
+        m = self._lib.hpso_dump(self._h, buf.ctypes.data)
+        return buf[:m].copy()
+
+    def load_state(self, keys, ctr, vals=None):
+        """Overwrite the whole state (used to re-seat the oracle after an overflowing batch)."""
+        self.keys[...] = np.asarray(keys, dtype=np.int64).reshape(self.S, self.W)
+        self.ctr[...] = np.asarray(ctr, dtype=np.uint32).reshape(self.S)
+        if vals is not None:
+            v = np.asarray(vals)
+            if v.dtype == np.float32:
+                v = v.view(np.uint32)
+            self.vals[...] = v.reshape(self.S, self.W, self.d)
+
+
+def set_of(key: int, num_sets: int) -> int:
+    """Set index of a key for a cache with `num_sets` sets (same rule as the C file, via its mix64)."""
+    return (mix64(key) >> 32) % num_sets
