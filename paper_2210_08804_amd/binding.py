@@ -1,0 +1,180 @@
+"""Thin ctypes binding of include/hps_cache.h: argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Tensors are torch CUDA (ROCm)
+tensors used purely as device buffers; `stream` is a torch.cuda.Stream or None (= the current
+stream).  Nothing here computes anything and there is no CPU fallback: if the HIP library
+has not been built, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhps_cache.so")
+
+HPS_OK = 0
+HPS_ERR_INVALID_ARG = -1
+HPS_ERR_OOM = -2
+HPS_ERR_DEVICE = -3
+HPS_MAX_TABLES = 32
+
+EXPORTS = (
+    "hps_cache_create", "hps_cache_destroy", "hps_cache_query", "hps_cache_insert",
+    "hps_cache_update", "hps_last_error", "hps_cache_set_concurrent_writers", "hps_cache_info",
+    "hps_cache_export", "hps_cache_import", "hps_cache_dump", "hps_cache_query_multi",
+    "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn",
+)
+
+_lib = None
+
+
+class HpsError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"hps status {status}: {message}")
+        self.status = status
+
+
+def load_library():
+    """Load the built HIP library; raise if it is missing (build it with __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build the HIP extension first "
+            "(python -c 'import __graft_entry__ as g; g.build()'); there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, sz, u32 = C.c_void_p, C.c_size_t, C.c_uint32
+    lib.hps_last_error.restype = C.c_char_p
+    lib.hps_last_error.argtypes = []
+    sigs = {
+        "hps_cache_create": [sz, u32, u32, C.POINTER(vp)],
+        "hps_cache_destroy": [vp],
+        "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
+        "hps_cache_insert": [vp, vp, vp, sz, vp],
+        "hps_cache_update": [vp, vp, vp, sz, vp],
+        "hps_cache_set_concurrent_writers": [vp, C.c_int],
+        "hps_cache_info": [vp, C.POINTER(C.c_uint64), C.POINTER(u32), C.POINTER(u32)],
+        "hps_cache_export": [vp, vp, vp, vp, vp],
+        "hps_cache_import": [vp, vp, vp, vp, vp],
+        "hps_cache_dump": [vp, sz, sz, vp, vp, vp],
+        "hps_cache_query_multi": [C.POINTER(vp), u32, vp, sz, vp, vp, vp, vp, vp],
+        "hps_backing_fetch": [vp, sz, vp, u32, u32, vp, vp, vp, vp],
+        "hps_cache_insert_dn": [vp, vp, vp, sz, vp, vp],
+        "hps_cache_update_dn": [vp, vp, vp, sz, vp, vp],
+    }
+    for name, argtypes in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = argtypes
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != HPS_OK:
+        raise HpsError(status, load_library().hps_last_error().decode())
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("device tensor expected")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def hps_cache_create(capacity: int, ways: int, dim: int) -> int:
+    h = C.c_void_p()
+    _check(load_library().hps_cache_create(capacity, ways, dim, C.byref(h)))
+    return h.value
+
+
+def hps_cache_destroy(handle) -> None:
+    _check(load_library().hps_cache_destroy(handle))
+
+
+def hps_cache_query(handle, keys, n, out, miss_idx, miss_keys, n_miss, stream=None) -> None:
+    _check(load_library().hps_cache_query(
+        handle, _ptr(keys, torch.int64), n, _ptr(out, torch.float32), _ptr(miss_idx, torch.int32),
+        _ptr(miss_keys, torch.int64), _ptr(n_miss, torch.int32), _stream(stream)))
+
+
+def hps_cache_insert(handle, keys, vals, n, stream=None) -> None:
+    _check(load_library().hps_cache_insert(
+        handle, _ptr(keys, torch.int64), _ptr(vals, torch.float32), n, _stream(stream)))
+
+
+def hps_cache_update(handle, keys, vals, n, stream=None) -> None:
+    _check(load_library().hps_cache_update(
+        handle, _ptr(keys, torch.int64), _ptr(vals, torch.float32), n, _stream(stream)))
+
+
+def hps_cache_insert_dn(handle, keys, vals, n_max, n_dev, stream=None) -> None:
+    _check(load_library().hps_cache_insert_dn(
+        handle, _ptr(keys, torch.int64), _ptr(vals, torch.float32), n_max,
+        _ptr(n_dev, torch.int32), _stream(stream)))
+
+
+def hps_cache_update_dn(handle, keys, vals, n_max, n_dev, stream=None) -> None:
+    _check(load_library().hps_cache_update_dn(
+        handle, _ptr(keys, torch.int64), _ptr(vals, torch.float32), n_max,
+        _ptr(n_dev, torch.int32), _stream(stream)))
+
+
+def hps_cache_set_concurrent_writers(handle, enabled: bool) -> None:
+    _check(load_library().hps_cache_set_concurrent_writers(handle, 1 if enabled else 0))
+
+
+def hps_cache_info(handle):
+    s, w, d = C.c_uint64(), C.c_uint32(), C.c_uint32()
+    _check(load_library().hps_cache_info(handle, C.byref(s), C.byref(w), C.byref(d)))
+    return s.value, w.value, d.value
+
+
+def hps_cache_export(handle, keys, ctr, vals=None, stream=None) -> None:
+    _check(load_library().hps_cache_export(
+        handle, _ptr(keys, torch.int64), _ptr(ctr, torch.int32), _ptr(vals, torch.float32),
+        _stream(stream)))
+
+
+def hps_cache_import(handle, keys, ctr, vals=None, stream=None) -> None:
+    _check(load_library().hps_cache_import(
+        handle, _ptr(keys, torch.int64), _ptr(ctr, torch.int32), _ptr(vals, torch.float32),
+        _stream(stream)))
+
+
+def hps_cache_dump(handle, first_slot, n_slots, keys_out, n_out, stream=None) -> None:
+    _check(load_library().hps_cache_dump(
+        handle, first_slot, n_slots, _ptr(keys_out, torch.int64), _ptr(n_out, torch.int32),
+        _stream(stream)))
+
+
+def hps_cache_query_multi(handles, keys, batch, out, miss_idx, miss_keys, n_miss, stream=None) -> None:
+    arr = (C.c_void_p * len(handles))(*handles)
+    _check(load_library().hps_cache_query_multi(
+        arr, len(handles), _ptr(keys, torch.int64), batch, _ptr(out, torch.float32),
+        _ptr(miss_idx, torch.int32), _ptr(miss_keys, torch.int64), _ptr(n_miss, torch.int32),
+        _stream(stream)))
+
+
+def hps_backing_fetch(keys, n, dim, version=0, rows=None, n_dev=None, scatter_idx=None,
+                      scatter_out=None, stream=None) -> None:
+    _check(load_library().hps_backing_fetch(
+        _ptr(keys, torch.int64), n, _ptr(n_dev, torch.int32), dim, version,
+        _ptr(rows, torch.float32), _ptr(scatter_idx, torch.int32),
+        _ptr(scatter_out, torch.float32), _stream(stream)))
+
+
+def hps_last_error() -> str:
+    return load_library().hps_last_error().decode()

@@ -1,0 +1,786 @@
+// GPU embedding cache for MI355X (gfx950, wave64): kernels and the C ABI of include/hps_cache.h.
+//
+// Memory layout (all in HBM, owned by the cache):
+//   K   int64  [S][W]      keys, one 64-byte line per set at W = 8; EMPTY = INT64_MIN
+//   V   fp32   [S][W][d]   rows, 16-byte aligned, moved as opaque 128-bit chunks
+//   ctr uint32 [S]         victim counter: next way of the set = ctr mod W
+//   seq uint32 [S]         sequence word: odd while a writer owns the set (lock + seqlock)
+//
+// Paper passages: data model Sec. 4.1; Query Alg. 2; Replace Alg. 3; Update Alg. 4; Dump and
+// the asynchronous, batch-in calling convention Sec. 4.2.  The paper's per-slabset warp lock
+// (Sec. 4.1) survives as the per-set sequence word, but only writers take it: query is
+// read-only because the victim rule keeps no access stamps.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <climits>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "hps_cache.h"
+
+namespace {
+
+constexpr int64_t  kEmpty      = INT64_MIN;
+constexpr int      kBlock      = 256;          // threads per work-group: 4 waves of 64
+constexpr int      kWave       = 64;
+constexpr int      kWavesPerWg = kBlock / kWave;
+constexpr uint32_t kRing       = 1024;         // per-call counter slots (see QueryArgs::slot)
+constexpr uint64_t kMagic      = 0x4850534341434845ull;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk of a row
+
+thread_local std::string g_err;
+
+hps_status_t fail(hps_status_t code, const std::string &msg) {
+    g_err = msg;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return fail(e_ == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE,        \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));              \
+    } while (0)
+
+// ------------------------------------------------------------------ device helpers
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+// Alg. 2 "slabsetHasher(q) mod |S|": upper hash half modulo the set count (mask when S is 2^k).
+__device__ __forceinline__ uint32_t set_of(int64_t key, uint32_t S, uint32_t smask) {
+    uint32_t h = (uint32_t)(mix64((uint64_t)key) >> 32);
+    return smask ? (h & smask) : (h % S);
+}
+
+__device__ __forceinline__ bool is_reserved(int64_t key) { return key < kEmpty + 2; }
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
+    int lo = __shfl((int)(uint32_t)(uint64_t)v, src, kWave);
+    int hi = __shfl((int)(uint32_t)((uint64_t)v >> 32), src, kWave);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// Number of set bits of m below this lane.
+__device__ __forceinline__ int rank_in(uint64_t m) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// Orders this wave's LDS traffic against itself (no instructions, compiler-only).
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <typename T> __device__ __forceinline__ T ld_agent(const T *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ void st_agent(T *p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct Table {                 // one cache as the kernels see it
+    int64_t  *K;
+    float    *V;
+    uint32_t *ctr;
+    uint32_t *seq;
+    uint32_t  S;
+    uint32_t  smask;           // S - 1 when S is a power of two, else 0
+};
+
+// Row geometry shared by all copy loops: a row is C = d/4 chunks of 16 bytes; LPR lanes
+// cooperate on one row (16 B per lane, contiguous, so a wave load covers 64/LPR whole rows).
+struct RowGeom {
+    uint32_t d;                // fp32 per row
+    uint32_t C;                // 16-byte chunks per row
+    uint32_t LPR;              // lanes per row: min(64, next power of two >= C)
+    uint32_t lprShift;         // log2(LPR)
+    uint32_t passes;           // ceil(C / LPR): > 1 only for rows longer than 1 KiB
+};
+
+// Set probe for the 64 keys of a wave (Alg. 2 "warpReadOutSlab" + match): W lanes read the W
+// slot keys of one set (contiguous 8*W bytes), so one wave load covers 64/W sets; a ballot
+// over the equality test gives every key its way.  Returns the way or -1.
+template <int W>
+__device__ __forceinline__ int probe_wave(const int64_t *__restrict__ K, int64_t key,
+                                          uint32_t set, bool want) {
+    constexpr int G = kWave / W;               // keys per wave load
+    const int lane = lane_id();
+    const int slot = lane & (W - 1);
+    const int sub  = lane / W;
+    int64_t sk[W];
+#pragma unroll
+    for (int r = 0; r < W; ++r) {
+        const int j = r * G + sub;
+        const uint32_t sj = (uint32_t)__shfl((int)set, j, kWave);
+        const int wj = __shfl((int)want, j, kWave);
+        sk[r] = wj ? K[(uint64_t)sj * W + slot] : kEmpty;
+    }
+    int way = -1;
+#pragma unroll
+    for (int r = 0; r < W; ++r) {
+        const int j = r * G + sub;
+        const int64_t kj = shfl64(key, j);
+        const int wj = __shfl((int)want, j, kWave);
+        const uint64_t m = __ballot(wj && sk[r] == kj);
+        if (lane / G == r) {
+            const uint64_t field = (W == 64) ? m : ((m >> ((lane % G) * W)) & ((1ull << (W & 63)) - 1));
+            if (field) way = __builtin_ctzll(field);
+        }
+    }
+    return way;
+}
+
+// ------------------------------------------------------------------ query
+
+struct QueryArgs {
+    Table          tab[HPS_MAX_TABLES];
+    const int64_t *keys;        // [T][B]
+    float         *out;         // [T][B][d]
+    uint32_t      *miss_idx;
+    int64_t       *miss_keys;
+    uint32_t      *n_miss;
+    uint64_t      *slot;        // per-call counter word: low 32 bits = misses so far, high 32 = tiles done
+    uint32_t       B;           // keys per table
+    uint32_t       tiles_per_table;
+    uint32_t       n_tiles;     // T * tiles_per_table (>= 1 even when B == 0)
+    RowGeom        g;
+};
+
+// One work-group handles tiles of 256 positions, one key per lane.
+//   phase 1  load key, hash, probe the set (probe_wave)
+//   phase 2  misses: wave prefix sums (ballot + mbcnt), wave totals combined in LDS, one
+//            64-bit atomic per tile on the call's counter word, which also counts finished
+//            tiles; the last tile publishes *n_miss and clears the word for the next call
+//   phase 3  hits: each wave compacts <source slot, destination position> pairs into its LDS
+//            list, then copies rows LPR lanes per row with U row-groups in flight
+template <int W, int U>
+__global__ void __launch_bounds__(kBlock) query_kernel(const QueryArgs a) {
+    __shared__ uint64_t s_src[kWavesPerWg][kWave];
+    __shared__ uint32_t s_dst[kWavesPerWg][kWave];
+    __shared__ uint32_t s_wcnt[kWavesPerWg];
+    __shared__ uint32_t s_base;
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    const RowGeom g = a.g;
+    const uint32_t rpi = kWave >> g.lprShift;          // rows per wave load
+    const uint32_t sub = (uint32_t)lane >> g.lprShift;  // which of those rows this lane serves
+    const uint32_t cl  = (uint32_t)lane & (g.LPR - 1);  // chunk of the row this lane moves
+
+    for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+        const uint32_t t    = tile / a.tiles_per_table;
+        const uint32_t lt   = tile - t * a.tiles_per_table;
+        const Table   &tb   = a.tab[t];
+        const uint32_t b    = lt * kBlock + threadIdx.x;
+        const bool     live = b < a.B;
+        const uint32_t pos  = t * a.B + b;             // position in keys/out (< 2^32 checked on host)
+
+        const int64_t key  = live ? a.keys[pos] : kEmpty;
+        const bool    want = live && !is_reserved(key);
+        const uint32_t set = want ? set_of(key, tb.S, tb.smask) : 0u;
+        const int      way = probe_wave<W>(tb.K, key, set, want);
+        const bool     hit = way >= 0;
+
+        // ---- phase 2: count misses
+        const uint64_t missmask = __ballot(live && !hit);
+        const uint32_t wmiss    = (uint32_t)__popcll(missmask);
+        if (lane == 0) s_wcnt[wave] = wmiss;
+
+        // ---- phase 3 (list build): hits of this wave, compacted
+        const uint64_t hitmask = __ballot(hit);
+        const uint32_t nh      = (uint32_t)__popcll(hitmask);
+        if (hit) {
+            const int r = rank_in(hitmask);
+            s_src[wave][r] = (uint64_t)set * W + (uint32_t)way;
+            s_dst[wave][r] = pos;
+        }
+        __syncthreads();
+
+        uint32_t woff = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerWg; ++w) {
+            const uint32_t c = s_wcnt[w];
+            woff += (w < wave) ? c : 0u;
+            total += c;
+        }
+        uint64_t old = 0;
+        if (threadIdx.x == 0)
+            old = __hip_atomic_fetch_add(a.slot, (1ull << 32) | (uint64_t)total, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+
+        // ---- phase 3 (copy): rows of this wave's hits
+        const float *__restrict__ V = tb.V;
+        for (uint32_t pass = 0; pass < g.passes; ++pass) {
+            const uint32_t chunk = cl + pass * g.LPR;
+            const bool cok = chunk < g.C;
+            for (uint32_t e0 = 0; e0 < nh; e0 += rpi * U) {
+                f32x4 buf[U];
+                uint32_t dpos[U];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t e = e0 + u * rpi + sub;
+                    ok[u] = cok && e < nh;
+                    if (ok[u]) {
+                        const uint64_t src = s_src[wave][e];
+                        dpos[u] = s_dst[wave][e];
+                        buf[u] = *reinterpret_cast<const f32x4 *>(V + src * g.d + chunk * 4);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (ok[u])
+                        __builtin_nontemporal_store(
+                            buf[u], reinterpret_cast<f32x4 *>(a.out + (uint64_t)dpos[u] * g.d + chunk * 4));
+            }
+        }
+
+        // ---- phase 2 (write): miss list entries of this tile
+        if (threadIdx.x == 0) {
+            s_base = (uint32_t)old;
+            if ((uint32_t)(old >> 32) + 1u == a.n_tiles) {          // every tile has added its count
+                *a.n_miss = (uint32_t)old + total;
+                __hip_atomic_store(a.slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();
+        if (live && !hit) {
+            const uint32_t o = s_base + woff + (uint32_t)rank_in(missmask);
+            a.miss_idx[o]  = pos;
+            a.miss_keys[o] = key;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ insert / update
+
+struct WriteArgs {
+    Table           tab;
+    const int64_t  *keys;
+    const float    *vals;
+    const uint32_t *n_dev;      // optional device-side batch length
+    uint32_t        n;
+    RowGeom         g;
+};
+
+// Replace (Alg. 3) and Update (Alg. 4).  One key per lane.  A lane that has to write takes its
+// set's sequence word from even to odd with a compare-and-swap (the paper's slabset lock,
+// Sec. 4.1), after an optimistic search of the set: the swap succeeds only if no other writer
+// finished in between, so the search result still holds under the lock.  Lanes never wait while
+// the wave holds a lock: each round every pending lane tries once, the winners' rows are copied
+// by the whole wave, the locks are released, and the losers try again.
+//   insert: key found -> ignored; else way = ctr mod W, ctr += 1, key and row written
+//   update: key not found -> ignored; else row overwritten
+template <int W, bool kInsert>
+__global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
+    __shared__ uint64_t s_dst[kWavesPerWg][kWave];
+    __shared__ uint32_t s_srcrow[kWavesPerWg][kWave];
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    const RowGeom g = a.g;
+    const Table tb = a.tab;
+    const uint32_t rpi = kWave >> g.lprShift;
+    const uint32_t sub = (uint32_t)lane >> g.lprShift;
+    const uint32_t cl  = (uint32_t)lane & (g.LPR - 1);
+    uint32_t n = a.n;
+    if (a.n_dev) {
+        const uint32_t nd = *a.n_dev;
+        n = nd < n ? nd : n;
+    }
+    const uint32_t n_tiles = (n + kWave - 1) / kWave;
+    const uint32_t wave_global = blockIdx.x * kWavesPerWg + wave;
+    const uint32_t n_waves = gridDim.x * kWavesPerWg;
+
+    for (uint32_t tile = wave_global; tile < n_tiles; tile += n_waves) {
+        const uint32_t i = tile * kWave + lane;
+        const int64_t key = i < n ? a.keys[i] : kEmpty;
+        bool pending = i < n && !is_reserved(key);
+        const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
+
+        while (__ballot(pending)) {
+            bool won = false;
+            uint32_t v = 0;
+            int way = -1;
+            if (pending) {
+                v = ld_agent(tb.seq + set);
+                if (!(v & 1u)) {
+#pragma unroll
+                    for (int w = 0; w < W; ++w)
+                        if (ld_agent(tb.K + (uint64_t)set * W + w) == key) way = w;
+                    const bool found = way >= 0;
+                    if (found == kInsert) {
+                        pending = false;                      // insert: already cached; update: absent
+                    } else {
+                        uint32_t expect = v;
+                        won = __hip_atomic_compare_exchange_strong(
+                            tb.seq + set, &expect, v + 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                            __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+            const uint64_t wonmask = __ballot(won);
+            if (wonmask) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                if (won) {
+                    if (kInsert) {
+                        const uint32_t c = ld_agent(tb.ctr + set);
+                        way = (int)(c & (W - 1));
+                        st_agent(tb.ctr + set, c + 1u);
+                        st_agent(tb.K + (uint64_t)set * W + way, key);
+                    }
+                    const int r = rank_in(wonmask);
+                    s_dst[wave][r] = (uint64_t)set * W + (uint32_t)way;
+                    s_srcrow[wave][r] = i;
+                }
+                wave_lds_fence();
+                const uint32_t nw = (uint32_t)__popcll(wonmask);
+                for (uint32_t pass = 0; pass < g.passes; ++pass) {
+                    const uint32_t chunk = cl + pass * g.LPR;
+                    for (uint32_t e = sub; e < nw; e += rpi) {
+                        if (chunk < g.C) {
+                            const f32x4 x = *reinterpret_cast<const f32x4 *>(
+                                a.vals + (uint64_t)s_srcrow[wave][e] * g.d + chunk * 4);
+                            *reinterpret_cast<f32x4 *>(tb.V + s_dst[wave][e] * g.d + chunk * 4) = x;
+                        }
+                    }
+                }
+                wave_lds_fence();
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                if (won) {
+                    st_agent(tb.seq + set, v + 2u);
+                    pending = false;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ small kernels
+
+__global__ void fill_keys_kernel(int64_t *K, uint64_t n, int64_t v) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        K[i] = v;
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// Dump (Sec. 4.2): compact the non-empty keys of a slot range.  Same counter-word scheme as query.
+__global__ void __launch_bounds__(kBlock) dump_kernel(const int64_t *__restrict__ K, uint64_t first,
+                                                      uint64_t n_slots, int64_t *keys_out,
+                                                      uint32_t *n_out, uint64_t *slot,
+                                                      uint32_t n_tiles) {
+    __shared__ uint32_t s_wcnt[kWavesPerWg];
+    __shared__ uint32_t s_base;
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t i = (uint64_t)tile * kBlock + threadIdx.x;
+        const int64_t key = i < n_slots ? K[first + i] : kEmpty;
+        const bool full = key != kEmpty;
+        const uint64_t m = __ballot(full);
+        if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t woff = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerWg; ++w) {
+            const uint32_t c = s_wcnt[w];
+            woff += (w < wave) ? c : 0u;
+            total += c;
+        }
+        if (threadIdx.x == 0) {
+            const uint64_t old = __hip_atomic_fetch_add(slot, (1ull << 32) | (uint64_t)total,
+                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_base = (uint32_t)old;
+            if ((uint32_t)(old >> 32) + 1u == n_tiles) {
+                *n_out = (uint32_t)old + total;
+                __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();
+        if (full) keys_out[s_base + woff + (uint32_t)rank_in(m)] = key;
+    }
+}
+
+// Lower-tier stand-in: four consecutive elements of one row per thread.
+__global__ void backing_kernel(const int64_t *__restrict__ keys, uint32_t n,
+                               const uint32_t *__restrict__ n_dev, uint32_t d, uint32_t version,
+                               float *rows, const uint32_t *__restrict__ scatter_idx,
+                               float *scatter_out) {
+    if (n_dev) {
+        const uint32_t nd = *n_dev;
+        n = nd < n ? nd : n;
+    }
+    const uint32_t C = d / 4;
+    const uint64_t total = (uint64_t)n * C;
+    for (uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; t < total;
+         t += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t i = (uint32_t)(t / C);
+        const uint32_t c = (uint32_t)(t - (uint64_t)i * C);
+        const uint64_t k = (uint64_t)keys[i];
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint64_t j = c * 4 + e;
+            const uint64_t z = mix64(k ^ mix64((((uint64_t)version << 32) | j) + 0x9E3779B97F4A7C15ull));
+            x[e] = (float)((int32_t)(z >> 40) - (1 << 23)) * 0x1.0p-23f;   // exact: 24-bit integer * 2^-23
+        }
+        const f32x4 v4 = {x[0], x[1], x[2], x[3]};
+        if (rows) *reinterpret_cast<f32x4 *>(rows + (uint64_t)i * d + c * 4) = v4;
+        if (scatter_idx)
+            *reinterpret_cast<f32x4 *>(scatter_out + (uint64_t)scatter_idx[i] * d + c * 4) = v4;
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+RowGeom make_geom(uint32_t d) {
+    RowGeom g;
+    g.d = d;
+    g.C = d / 4;
+    uint32_t lpr = 1, sh = 0;
+    while (lpr < g.C && lpr < (uint32_t)kWave) { lpr <<= 1; ++sh; }
+    g.LPR = lpr;
+    g.lprShift = sh;
+    g.passes = (g.C + lpr - 1) / lpr;
+    return g;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+}  // namespace
+
+struct hps_cache {
+    uint64_t magic;
+    int      device;
+    uint64_t S;
+    uint32_t W, d;
+    int64_t  *K;
+    float    *V;
+    uint32_t *ctr;
+    uint32_t *seq;
+    uint64_t *ring;                       // kRing counter words, all zero between calls
+    std::atomic<uint32_t> calls;
+    std::atomic<int> concurrent_writers;
+};
+
+namespace {
+
+hps_status_t check_handle(const hps_cache *c) {
+    if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != c->device)
+        return fail(HPS_ERR_INVALID_ARG, "cache was created on device " + std::to_string(c->device) +
+                                             " but device " + std::to_string(dev) + " is current");
+    return HPS_OK;
+}
+
+Table table_of(const hps_cache *c) {
+    Table t;
+    t.K = c->K;
+    t.V = c->V;
+    t.ctr = c->ctr;
+    t.seq = c->seq;
+    t.S = (uint32_t)c->S;
+    t.smask = (c->S & (c->S - 1)) == 0 ? (uint32_t)(c->S - 1) : 0u;
+    if (c->S == 1) t.smask = 0;           // S = 1: "h % 1" = 0 (a zero mask means "use modulo")
+    return t;
+}
+
+uint64_t *next_slot(hps_cache *c) {
+    return c->ring + (c->calls.fetch_add(1, std::memory_order_relaxed) % kRing);
+}
+
+template <int W>
+void launch_query_w(const QueryArgs &a, uint32_t grid, hipStream_t st) {
+    hipLaunchKernelGGL((query_kernel<W, 8>), dim3(grid), dim3(kBlock), 0, st, a);
+}
+
+hps_status_t launch_query(uint32_t W, const QueryArgs &a, hipStream_t st) {
+    const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
+    switch (W) {
+        case 1:  launch_query_w<1>(a, grid, st); break;
+        case 2:  launch_query_w<2>(a, grid, st); break;
+        case 4:  launch_query_w<4>(a, grid, st); break;
+        case 8:  launch_query_w<8>(a, grid, st); break;
+        case 16: launch_query_w<16>(a, grid, st); break;
+        case 32: launch_query_w<32>(a, grid, st); break;
+        case 64: launch_query_w<64>(a, grid, st); break;
+        default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
+    }
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+template <bool kInsert>
+hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, size_t n,
+                          const uint32_t *n_dev, hipStream_t st) {
+    WriteArgs a;
+    a.tab = table_of(c);
+    a.keys = keys;
+    a.vals = vals;
+    a.n_dev = n_dev;
+    a.n = (uint32_t)n;
+    a.g = make_geom(c->d);
+    const uint64_t tiles = (n + kWave - 1) / kWave;
+    uint64_t blocks = (tiles + kWavesPerWg - 1) / kWavesPerWg;
+    if (blocks > (1u << 16)) blocks = 1u << 16;
+    const dim3 grid((uint32_t)blocks), block(kBlock);
+    switch (c->W) {
+#define HPS_CASE(w) case w: hipLaunchKernelGGL((write_kernel<w, kInsert>), grid, block, 0, st, a); break;
+        HPS_CASE(1) HPS_CASE(2) HPS_CASE(4) HPS_CASE(8) HPS_CASE(16) HPS_CASE(32) HPS_CASE(64)
+#undef HPS_CASE
+        default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
+    }
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t write_call(hps_cache *c, const int64_t *keys, const float *vals, size_t n,
+                        const uint32_t *n_dev, void *stream, bool insert) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (n == 0) return HPS_OK;
+    if (n >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n must be < 2^32");
+    if (!keys || !vals) return fail(HPS_ERR_INVALID_ARG, "keys/vals must not be NULL when n > 0");
+    if (!aligned(keys, 8) || !aligned(vals, 16) || !aligned(n_dev, 4))
+        return fail(HPS_ERR_INVALID_ARG, "keys must be 8-byte and vals 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return insert ? launch_write<true>(c, keys, vals, n, n_dev, st)
+                  : launch_write<false>(c, keys, vals, n, n_dev, st);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" {
+
+const char *hps_last_error(void) { return g_err.c_str(); }
+
+hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim, hps_cache_t **out_handle) {
+    if (!out_handle) return fail(HPS_ERR_INVALID_ARG, "out_handle is NULL");
+    *out_handle = nullptr;
+    if (ways == 0 || ways > 64 || (ways & (ways - 1)) != 0)
+        return fail(HPS_ERR_INVALID_ARG, "ways must be a power of two in [1, 64]");
+    if (capacity == 0 || capacity % ways != 0)
+        return fail(HPS_ERR_INVALID_ARG, "capacity must be a non-zero multiple of ways");
+    if (capacity / ways >= (1ull << 31))
+        return fail(HPS_ERR_INVALID_ARG, "capacity / ways must be < 2^31");
+    if (dim == 0 || dim % 4 != 0) return fail(HPS_ERR_INVALID_ARG, "dim must be a non-zero multiple of 4");
+
+    hps_cache *c = new (std::nothrow) hps_cache();
+    if (!c) return fail(HPS_ERR_OOM, "host allocation failed");
+    c->magic = kMagic;
+    c->S = capacity / ways;
+    c->W = ways;
+    c->d = dim;
+    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr;
+    c->calls.store(0);
+    c->concurrent_writers.store(1);
+
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipMalloc(&c->K, capacity * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMalloc(&c->V, capacity * (size_t)dim * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&c->ctr, c->S * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(&c->seq, c->S * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(&c->ring, kRing * sizeof(uint64_t));
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(fill_keys_kernel, dim3(4096), dim3(256), 0, 0, c->K, (uint64_t)capacity, kEmpty);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemsetAsync(c->V, 0, capacity * (size_t)dim * sizeof(float), 0);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ctr, 0, c->S * sizeof(uint32_t), 0);
+    if (e == hipSuccess) e = hipMemsetAsync(c->seq, 0, c->S * sizeof(uint32_t), 0);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ring, 0, kRing * sizeof(uint64_t), 0);
+    if (e == hipSuccess) e = hipStreamSynchronize(0);
+    if (e != hipSuccess) {
+        const hps_status_t code = e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE;
+        std::string msg = std::string("hps_cache_create: ") + hipGetErrorString(e);
+        (void)hipGetLastError();
+        if (c->K) (void)hipFree(c->K);
+        if (c->V) (void)hipFree(c->V);
+        if (c->ctr) (void)hipFree(c->ctr);
+        if (c->seq) (void)hipFree(c->seq);
+        if (c->ring) (void)hipFree(c->ring);
+        delete c;
+        return fail(code, msg);
+    }
+    *out_handle = c;
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_destroy(hps_cache_t *c) {
+    if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    c->magic = 0;
+    hipError_t e = hipSuccess, e2;
+    if ((e2 = hipFree(c->K)) != hipSuccess) e = e2;
+    if ((e2 = hipFree(c->V)) != hipSuccess) e = e2;
+    if ((e2 = hipFree(c->ctr)) != hipSuccess) e = e2;
+    if ((e2 = hipFree(c->seq)) != hipSuccess) e = e2;
+    if ((e2 = hipFree(c->ring)) != hipSuccess) e = e2;
+    delete c;
+    if (e != hipSuccess) return fail(HPS_ERR_DEVICE, std::string("hipFree: ") + hipGetErrorString(e));
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_info(const hps_cache_t *c, uint64_t *num_sets, uint32_t *ways, uint32_t *dim) {
+    if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    if (num_sets) *num_sets = c->S;
+    if (ways) *ways = c->W;
+    if (dim) *dim = c->d;
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *c, int enabled) {
+    if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    c->concurrent_writers.store(enabled ? 1 : 0);
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables, const int64_t *keys,
+                                   size_t batch, float *out, uint32_t *miss_idx, int64_t *miss_keys,
+                                   uint32_t *n_miss, void *stream) {
+    if (!caches || n_tables == 0 || n_tables > HPS_MAX_TABLES)
+        return fail(HPS_ERR_INVALID_ARG, "n_tables must be in [1, HPS_MAX_TABLES]");
+    for (uint32_t t = 0; t < n_tables; ++t) {
+        if (hps_status_t s = check_handle(caches[t])) return s;
+        if (caches[t]->d != caches[0]->d || caches[t]->W != caches[0]->W)
+            return fail(HPS_ERR_INVALID_ARG, "all tables of one call must share dim and ways");
+    }
+    if (!n_miss || !aligned(n_miss, 4)) return fail(HPS_ERR_INVALID_ARG, "n_miss must be a 4-byte aligned device pointer");
+    const uint64_t total = (uint64_t)n_tables * batch;
+    if (total >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n_tables * batch must be < 2^32");
+    if (total > 0) {
+        if (!keys || !out || !miss_idx || !miss_keys)
+            return fail(HPS_ERR_INVALID_ARG, "keys/out/miss_idx/miss_keys must not be NULL when n > 0");
+        if (!aligned(keys, 8) || !aligned(miss_keys, 8) || !aligned(out, 16) || !aligned(miss_idx, 4))
+            return fail(HPS_ERR_INVALID_ARG, "misaligned buffer (keys 8, out 16, miss_idx 4 bytes)");
+    }
+    QueryArgs a;
+    std::memset(&a, 0, sizeof(a));
+    for (uint32_t t = 0; t < n_tables; ++t) a.tab[t] = table_of(caches[t]);
+    a.keys = keys;
+    a.out = out;
+    a.miss_idx = miss_idx;
+    a.miss_keys = miss_keys;
+    a.n_miss = n_miss;
+    a.slot = next_slot(caches[0]);
+    a.B = (uint32_t)batch;
+    a.tiles_per_table = (uint32_t)((batch + kBlock - 1) / kBlock);
+    if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
+    a.n_tiles = a.tiles_per_table * n_tables;
+    a.g = make_geom(caches[0]->d);
+    return launch_query(caches[0]->W, a, static_cast<hipStream_t>(stream));
+}
+
+hps_status_t hps_cache_query(hps_cache_t *c, const int64_t *keys, size_t n, float *out,
+                             uint32_t *miss_idx, int64_t *miss_keys, uint32_t *n_miss, void *stream) {
+    if (n >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n must be < 2^32");
+    hps_cache_t *one[1] = {c};
+    return hps_cache_query_multi(one, 1, keys, n, out, miss_idx, miss_keys, n_miss, stream);
+}
+
+hps_status_t hps_cache_insert(hps_cache_t *c, const int64_t *keys, const float *vals, size_t n, void *stream) {
+    return write_call(c, keys, vals, n, nullptr, stream, true);
+}
+hps_status_t hps_cache_update(hps_cache_t *c, const int64_t *keys, const float *vals, size_t n, void *stream) {
+    return write_call(c, keys, vals, n, nullptr, stream, false);
+}
+hps_status_t hps_cache_insert_dn(hps_cache_t *c, const int64_t *keys, const float *vals, size_t n_max,
+                                 const uint32_t *n_dev, void *stream) {
+    if (!n_dev) return fail(HPS_ERR_INVALID_ARG, "n_dev is NULL");
+    return write_call(c, keys, vals, n_max, n_dev, stream, true);
+}
+hps_status_t hps_cache_update_dn(hps_cache_t *c, const int64_t *keys, const float *vals, size_t n_max,
+                                 const uint32_t *n_dev, void *stream) {
+    if (!n_dev) return fail(HPS_ERR_INVALID_ARG, "n_dev is NULL");
+    return write_call(c, keys, vals, n_max, n_dev, stream, false);
+}
+
+hps_status_t hps_cache_export(hps_cache_t *c, int64_t *keys, uint32_t *ctr, float *vals, void *stream) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (!keys || !ctr) return fail(HPS_ERR_INVALID_ARG, "keys and ctr must not be NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t slots = c->S * c->W;
+    HIP_TRY(hipMemcpyAsync(keys, c->K, slots * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ctr, c->ctr, c->S * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    if (vals)
+        HIP_TRY(hipMemcpyAsync(vals, c->V, slots * c->d * sizeof(float), hipMemcpyDeviceToDevice, st));
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_import(hps_cache_t *c, const int64_t *keys, const uint32_t *ctr, const float *vals,
+                              void *stream) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (!keys || !ctr) return fail(HPS_ERR_INVALID_ARG, "keys and ctr must not be NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t slots = c->S * c->W;
+    HIP_TRY(hipMemcpyAsync(c->K, keys, slots * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipMemcpyAsync(c->ctr, ctr, c->S * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    if (vals)
+        HIP_TRY(hipMemcpyAsync(c->V, vals, slots * c->d * sizeof(float), hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, c->seq, (uint64_t)c->S, 0u);
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_dump(hps_cache_t *c, size_t first_slot, size_t n_slots, int64_t *keys_out,
+                            uint32_t *n_out, void *stream) {
+    if (hps_status_t s = check_handle(c)) return s;
+    const size_t slots = c->S * c->W;
+    if (first_slot > slots || n_slots > slots - first_slot)
+        return fail(HPS_ERR_INVALID_ARG, "slot range exceeds the cache");
+    if (n_slots >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n_slots must be < 2^32 per call");
+    if (!n_out || (n_slots > 0 && !keys_out)) return fail(HPS_ERR_INVALID_ARG, "output pointer is NULL");
+    if (!aligned(keys_out, 8) || !aligned(n_out, 4)) return fail(HPS_ERR_INVALID_ARG, "misaligned output buffer");
+    uint32_t n_tiles = (uint32_t)((n_slots + kBlock - 1) / kBlock);
+    if (n_tiles == 0) n_tiles = 1;
+    const uint32_t grid = n_tiles < (1u << 16) ? n_tiles : (1u << 16);
+    hipLaunchKernelGGL(dump_kernel, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), c->K,
+                       (uint64_t)first_slot, (uint64_t)n_slots, keys_out, n_out, next_slot(c), n_tiles);
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t hps_backing_fetch(const int64_t *keys, size_t n, const uint32_t *n_dev, uint32_t dim,
+                               uint32_t version, float *rows, const uint32_t *scatter_idx,
+                               float *scatter_out, void *stream) {
+    if (dim == 0 || dim % 4 != 0) return fail(HPS_ERR_INVALID_ARG, "dim must be a non-zero multiple of 4");
+    if (n == 0) return HPS_OK;
+    if (n >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n must be < 2^32");
+    if (!keys || (!rows && !scatter_idx)) return fail(HPS_ERR_INVALID_ARG, "keys and one output are required");
+    if (scatter_idx && !scatter_out) return fail(HPS_ERR_INVALID_ARG, "scatter_out is NULL");
+    if (!aligned(keys, 8) || !aligned(rows, 16) || !aligned(scatter_out, 16) || !aligned(scatter_idx, 4))
+        return fail(HPS_ERR_INVALID_ARG, "misaligned buffer");
+    const uint64_t total = (uint64_t)n * (dim / 4);
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > (1u << 18)) blocks = 1u << 18;
+    hipLaunchKernelGGL(backing_kernel, dim3((uint32_t)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       keys, (uint32_t)n, n_dev, dim, version, rows, scatter_idx, scatter_out);
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+}  // extern "C"

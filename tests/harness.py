@@ -1,0 +1,168 @@
+"""Shared test plumbing: a numpy-facing wrapper of the C-ABI binding, canonical state
+comparison, and the rule that says when an insert batch has an order-independent result.
+
+Nothing here is arithmetic of the cache itself; the oracle side lives in oracle/, the GPU side
+behind paper_2210_08804_amd.binding.
+"""
+import collections
+
+import numpy as np
+import torch
+
+from paper_2210_08804_amd import binding as B
+
+EMPTY_KEY = -(1 << 63)
+RESERVED_KEY = -(1 << 63) + 1
+SENTINEL = 0x7FC0DEAD          # bit pattern pre-filled into `out` (a NaN payload): must survive on miss rows
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.view(dtype) if t.element_size() == torch.empty((), dtype=dtype).element_size() else t.to(dtype)
+    return t.cuda()
+
+
+class DeviceCache:
+    """numpy in / numpy out wrapper over the C ABI (one cache)."""
+
+    def __init__(self, capacity, ways, dim):
+        self.h = B.hps_cache_create(capacity, ways, dim)
+        self.S, self.W, self.d = B.hps_cache_info(self.h)
+        assert self.S * self.W == capacity and self.W == ways and self.d == dim
+
+    def close(self):
+        if self.h:
+            torch.cuda.synchronize()
+            B.hps_cache_destroy(self.h)
+            self.h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def query(self, keys, stream=None, raw=False):
+        """Returns (out[n, d] uint32 bit patterns with SENTINEL on untouched rows,
+        miss_idx sorted ascending, miss_keys in the same order)."""
+        keys = np.ascontiguousarray(keys, dtype=np.int64)
+        n = keys.shape[0]
+        dk = torch.from_numpy(keys).cuda() if n else torch.empty(0, dtype=torch.int64, device="cuda")
+        out = torch.full((max(n, 1), self.d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32)
+        mi = torch.full((max(n, 1),), -1, dtype=torch.int32, device="cuda")
+        mk = torch.full((max(n, 1),), 0x5A5A5A5A, dtype=torch.int64, device="cuda")
+        nm = torch.full((1,), 12345, dtype=torch.int32, device="cuda")
+        B.hps_cache_query(self.h, dk, n, out, mi, mk, nm, stream)
+        torch.cuda.synchronize()
+        m = int(nm.item()) & 0xFFFFFFFF
+        assert m <= n, (m, n)
+        out_np = out.view(torch.int32).cpu().numpy().view(np.uint32)[:n]
+        mi_np = mi.cpu().numpy().view(np.uint32)[:m]
+        mk_np = mk.cpu().numpy()[:m]
+        # entries past n_miss must not have been written beyond position n (buffer bound is n)
+        if raw:
+            return out_np, mi_np, mk_np
+        order = np.argsort(mi_np, kind="stable")
+        return out_np, mi_np[order], mk_np[order]
+
+    def insert(self, keys, rows, stream=None):
+        keys = np.ascontiguousarray(keys, dtype=np.int64)
+        n = keys.shape[0]
+        if n == 0:
+            B.hps_cache_insert(self.h, None, None, 0, stream)
+            return
+        rows = np.ascontiguousarray(rows).view(np.float32).reshape(n, self.d)
+        B.hps_cache_insert(self.h, torch.from_numpy(keys).cuda(), torch.from_numpy(rows).cuda(), n, stream)
+        torch.cuda.synchronize()
+
+    def update(self, keys, rows, stream=None):
+        keys = np.ascontiguousarray(keys, dtype=np.int64)
+        n = keys.shape[0]
+        if n == 0:
+            B.hps_cache_update(self.h, None, None, 0, stream)
+            return
+        rows = np.ascontiguousarray(rows).view(np.float32).reshape(n, self.d)
+        B.hps_cache_update(self.h, torch.from_numpy(keys).cuda(), torch.from_numpy(rows).cuda(), n, stream)
+        torch.cuda.synchronize()
+
+    def export(self, with_vals=True):
+        k = torch.empty(self.S * self.W, dtype=torch.int64, device="cuda")
+        c = torch.empty(self.S, dtype=torch.int32, device="cuda")
+        v = torch.empty(self.S * self.W * self.d, dtype=torch.float32, device="cuda") if with_vals else None
+        B.hps_cache_export(self.h, k, c, v)
+        torch.cuda.synchronize()
+        keys = k.cpu().numpy().reshape(self.S, self.W)
+        ctr = c.cpu().numpy().view(np.uint32)
+        vals = v.view(torch.int32).cpu().numpy().view(np.uint32).reshape(self.S, self.W, self.d) if with_vals else None
+        return keys, ctr, vals
+
+    def load(self, keys, ctr, vals=None):
+        k = torch.from_numpy(np.ascontiguousarray(keys, dtype=np.int64).reshape(-1)).cuda()
+        c = torch.from_numpy(np.ascontiguousarray(ctr, dtype=np.uint32).view(np.int32).reshape(-1)).cuda()
+        v = None
+        if vals is not None:
+            v = torch.from_numpy(np.ascontiguousarray(vals).view(np.float32).reshape(-1)).cuda()
+        B.hps_cache_import(self.h, k, c, v)
+        torch.cuda.synchronize()
+
+
+def canonical(keys, ctr, vals):
+    """Per set: the sorted list of (key, row bytes) of its occupied slots, plus the counter.
+    Which way a key sits in depends on arrival order and is not part of the comparison."""
+    S, W = keys.shape
+    order = np.argsort(keys, axis=1, kind="stable")
+    ks = np.take_along_axis(keys, order, axis=1)
+    vs = np.take_along_axis(vals, order[:, :, None], axis=1) if vals is not None else None
+    return ks, ctr.copy(), vs
+
+
+def assert_same_state(gpu_state, oracle, with_vals=True):
+    gk, gc, gv = gpu_state
+    ck, cc, cv = canonical(gk, gc, gv if with_vals else None)
+    ok_, oc, ov = canonical(np.array(oracle.keys), np.array(oracle.ctr), np.array(oracle.vals) if with_vals else None)
+    assert (cc == oc).all(), "victim counters differ"
+    assert (ck == ok_).all(), "resident key sets differ"
+    if with_vals:
+        occupied = ck != EMPTY_KEY
+        assert (cv[occupied] == ov[occupied]).all(), "rows differ"
+
+
+def check_state_invariants(keys, ctr, vals, set_of, expect_row=None):
+    """The invariant list that must hold for any legal execution order.
+    set_of(key) -> set index; expect_row(key) -> allowed rows (list of uint32 arrays) or None."""
+    S, W = keys.shape
+    flat = keys.reshape(-1)
+    res = flat[flat != EMPTY_KEY]
+    assert len(np.unique(res)) == len(res), "a key is resident twice"
+    assert RESERVED_KEY not in res
+    occ = np.minimum(ctr.astype(np.int64), W)
+    way = np.arange(W)[None, :]
+    assert ((keys != EMPTY_KEY) == (way < occ[:, None])).all(), "occupancy != min(counter, W) or holes"
+    ss, ww = np.nonzero(keys != EMPTY_KEY)
+    for s, w in zip(ss.tolist(), ww.tolist()):
+        k = int(keys[s, w])
+        assert set_of(k) == s, "key outside its set"
+        if expect_row is not None:
+            allowed = expect_row(k)
+            assert any((vals[s, w] == r).all() for r in allowed), "row is none of the rows written for its key"
+
+
+def insert_is_order_independent(oracle, keys):
+    """True when every execution order of this insert batch gives the same canonical state:
+    in each set the distinct new keys number at most W and the slots they will overwrite hold
+    no key that also occurs in the batch (such a key would be re-inserted in some orders only)."""
+    keys = np.asarray(keys, dtype=np.int64)
+    W = oracle.W
+    resident = set(np.array(oracle.keys).reshape(-1).tolist())
+    batch = set(keys.tolist())
+    new = [k for k in batch - resident if k not in (EMPTY_KEY, RESERVED_KEY)]
+    per_set = collections.Counter(oracle.set_of(k) for k in new)
+    for s, cnt in per_set.items():
+        if cnt > W:
+            return False
+        c0 = int(oracle.ctr[s])
+        for t in range(cnt):
+            if int(oracle.keys[s, (c0 + t) % W]) in batch:
+                return False
+    return True

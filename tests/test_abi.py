@@ -1,0 +1,62 @@
+"""The C-ABI library loads, exports every function the header declares, and rejects bad
+arguments before touching the GPU.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hps_cache.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hps_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2210_08804_amd import binding
+    return binding.load_library()
+
+
+def test_header_and_binding_list_the_same_entry_points():
+    from paper_2210_08804_amd import binding
+    assert declared_functions() == sorted(binding.EXPORTS)
+    for name in binding.EXPORTS:
+        assert callable(getattr(binding, name))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert {"hps_cache_create", "hps_cache_query", "hps_cache_insert", "hps_cache_update",
+            "hps_cache_destroy"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    h = C.c_void_p()
+    bad = [(0, 8, 128), (64, 3, 128), (64, 128, 128), (60, 8, 128), (64, 8, 0), (64, 8, 6),
+           ((1 << 31) * 8, 8, 4)]
+    for cap, ways, dim in bad:
+        assert lib.hps_cache_create(cap, ways, dim, C.byref(h)) == -1
+        assert h.value is None
+        assert len(lib.hps_last_error()) > 0
+    assert lib.hps_cache_create(64, 8, 128, None) == -1
+    assert lib.hps_cache_destroy(None) == -1
+    assert lib.hps_cache_info(None, None, None, None) == -1
+    assert lib.hps_cache_set_concurrent_writers(None, 1) == -1
+    assert lib.hps_cache_query_multi(None, 0, None, 0, None, None, None, None, None) == -1
+    assert lib.hps_backing_fetch(None, 5, None, 6, 0, None, None, None, None) == -1
+    assert lib.hps_backing_fetch(None, 5, None, 8, 0, None, None, None, None) == -1   # keys NULL
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    from paper_2210_08804_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.hps_cache_create(64, 8, 128)
