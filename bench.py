@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--coherent", type=int, default=0,
                    help="1: queries validate rows against concurrent writers (not needed for a query-only run)")
     p.add_argument("--graph", type=int, default=0, help="1: replay the timed launches from one HIP graph")
+    p.add_argument("--streams", type=int, default=4,
+                   help="also time the same batches issued round-robin over this many streams (0: skip)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-batches", type=int, default=100)
     p.add_argument("--calibrate-copy", action="store_true",
@@ -148,6 +150,32 @@ def main():
     ms_per_step = ms_total / a.steps
     mkeys = n / (ms_per_step * 1e-3) / 1e6
 
+    # ---- the same batches issued round-robin over several streams (concurrent inference workers
+    #      sharing one cache, Sec. 4.1): kernels of different batches overlap
+    multi = None
+    if a.streams > 1:
+        ss = [torch.cuda.Stream() for _ in range(a.streams)]
+        sps = [x.cuda_stream for x in ss]
+        mtimes = []
+        for rep in range(a.repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for x in ss:
+                x.wait_stream(stream)
+            for b in range(a.warmup, n_batches):
+                sp = sps[b % a.streams]
+                launch(b)
+            for x in ss:
+                stream.wait_stream(x)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            mtimes.append(e0.elapsed_time(e1))
+        sp = stream.cuda_stream
+        m_ms = float(np.median(mtimes)) / a.steps
+        multi = {"streams": a.streams, "ms_per_step": round(m_ms, 5),
+                 "value": round(n / (m_ms * 1e-3) / 1e6, 1), "unit": "Mkeys/s"}
+
     # ---- algorithmic bytes per launch (what the method must move), from the realised batches
     n_miss = nm.cpu().numpy()[a.warmup:].astype(np.int64)
     stat_b = list(range(a.warmup, n_batches, max(1, a.steps // 64)))
@@ -202,6 +230,11 @@ def main():
             "us_per_launch": round(ms_per_step * 1e3, 3),
         },
     }
+
+    if multi is not None:
+        multi["achieved_GBps"] = round(alg_bytes / (multi["ms_per_step"] * 1e-3) / 1e9, 1)
+        multi["frac_of_peak"] = round(multi["achieved_GBps"] / HBM_PEAK_GBS, 4)
+        result["concurrent_streams"] = multi
 
     # ---- CPU oracle on the host cores, bounded sample of the same batches
     if not a.no_cpu_baseline:

@@ -16,6 +16,7 @@
 #include <climits>
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -113,27 +114,74 @@ struct RowGeom {
     uint32_t passes;           // ceil(C / LPR): > 1 only for rows longer than 1 KiB
 };
 
-// Set probe for the 64 keys of a wave (Alg. 2 "warpReadOutSlab" + match): W lanes read the W
-// slot keys of one set (contiguous 8*W bytes), so one wave load covers 64/W sets; a ballot
-// over the equality test gives every key its way.  Returns the way or -1.
-template <int W>
+// Copy `cnt` (> 0) rows listed in LDS: row srcRow[e] of `src` to row dstRow[e] of `dst`, for
+// e < cnt.  LPR lanes move one row, 16 B per lane, so a wave load/store covers 64/LPR whole
+// rows; U wave loads are issued back to back before the first store.  The code is branch-free
+// inside a group: lanes beyond the list (or beyond the row, when d/4 is not a power of two)
+// repeat entry 0 / chunk 0, i.e. they store the same bytes to the same place as a live lane.
+template <int U, typename SrcIdx, typename DstIdx>
+__device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restrict__ src,
+                                          float *__restrict__ dst, const SrcIdx *srcRow,
+                                          const DstIdx *dstRow, uint32_t cnt, bool nontemporal = true) {
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t rpi = (uint32_t)kWave >> g.lprShift;      // rows per wave load
+    const uint32_t sub = lane >> g.lprShift;                 // which of those rows this lane serves
+    const uint32_t cl  = lane & (g.LPR - 1);                 // chunk of the row this lane moves
+    for (uint32_t pass = 0; pass < g.passes; ++pass) {
+        uint32_t chunk = cl + pass * g.LPR;
+        chunk = chunk < g.C ? chunk : 0u;
+        const uint32_t off = chunk * 4;
+        uint32_t e0 = 0;
+        for (; e0 + rpi * U <= cnt || (e0 < cnt && U == 1); e0 += rpi * U) {
+            f32x4 buf[U];
+            uint64_t dp[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t e = e0 + u * rpi + sub;
+                e = e < cnt ? e : 0u;
+                const uint64_t sr = (uint64_t)srcRow[e];
+                dp[u] = (uint64_t)dstRow[e];
+                buf[u] = *reinterpret_cast<const f32x4 *>(src + sr * g.d + off);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                f32x4 *q = reinterpret_cast<f32x4 *>(dst + dp[u] * g.d + off);
+                if (nontemporal) __builtin_nontemporal_store(buf[u], q);
+                else *q = buf[u];
+            }
+        }
+        for (; e0 < cnt; e0 += rpi) {                        // remainder, one wave load at a time
+            uint32_t e = e0 + sub;
+            e = e < cnt ? e : 0u;
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(src + (uint64_t)srcRow[e] * g.d + off);
+            f32x4 *q = reinterpret_cast<f32x4 *>(dst + (uint64_t)dstRow[e] * g.d + off);
+            if (nontemporal) __builtin_nontemporal_store(x, q);
+            else *q = x;
+        }
+    }
+}
+
+// Set probe for the first KPW lanes' keys of a wave (Alg. 2 "warpReadOutSlab" + match): W lanes
+// read the W slot keys of one set (contiguous 8*W bytes), so one wave load covers 64/W sets; a
+// ballot over the equality test gives every key its way.  Returns the way or -1.
+template <int W, int KPW>
 __device__ __forceinline__ int probe_wave(const int64_t *__restrict__ K, int64_t key,
                                           uint32_t set, bool want) {
-    constexpr int G = kWave / W;               // keys per wave load
+    constexpr int G = kWave / W;                       // keys per wave load
+    constexpr int R = (KPW + G - 1) / G;               // wave loads needed for KPW keys
     const int lane = lane_id();
     const int slot = lane & (W - 1);
     const int sub  = lane / W;
-    int64_t sk[W];
+    int64_t sk[R];
 #pragma unroll
-    for (int r = 0; r < W; ++r) {
+    for (int r = 0; r < R; ++r) {
         const int j = r * G + sub;
-        const uint32_t sj = (uint32_t)__shfl((int)set, j, kWave);
-        const int wj = __shfl((int)want, j, kWave);
-        sk[r] = wj ? K[(uint64_t)sj * W + slot] : kEmpty;
+        const uint32_t sj = (uint32_t)__shfl((int)set, j, kWave);   // 0 for lanes without a key: a valid set
+        sk[r] = K[(uint64_t)sj * W + slot];
     }
     int way = -1;
 #pragma unroll
-    for (int r = 0; r < W; ++r) {
+    for (int r = 0; r < R; ++r) {
         const int j = r * G + sub;
         const int64_t kj = shfl64(key, j);
         const int wj = __shfl((int)want, j, kWave);
@@ -162,109 +210,88 @@ struct QueryArgs {
     RowGeom        g;
 };
 
-// One work-group handles tiles of 256 positions, one key per lane.
-//   phase 1  load key, hash, probe the set (probe_wave)
-//   phase 2  misses: wave prefix sums (ballot + mbcnt), wave totals combined in LDS, one
-//            64-bit atomic per tile on the call's counter word, which also counts finished
-//            tiles; the last tile publishes *n_miss and clears the word for the next call
-//   phase 3  hits: each wave compacts <source slot, destination position> pairs into its LDS
-//            list, then copies rows LPR lanes per row with U row-groups in flight
-template <int W, int U>
-__global__ void __launch_bounds__(kBlock) query_kernel(const QueryArgs a) {
-    __shared__ uint64_t s_src[kWavesPerWg][kWave];
-    __shared__ uint32_t s_dst[kWavesPerWg][kWave];
-    __shared__ uint32_t s_wcnt[kWavesPerWg];
-    __shared__ uint32_t s_base;
+// Query (Alg. 2).  A work-group is WPB worker waves plus one helper wave and handles tiles of
+// WPB*KPW positions; the first KPW lanes of each worker wave own one key each.
+//   workers  load key, hash, probe the set (probe_wave); misses are compacted per wave into LDS
+//            (ballot + mbcnt prefix), hits into the wave's <source slot, destination position>
+//            list; after one barrier the wave copies its rows (copy_rows).
+//   helper   after the barrier adds the tile's miss count to the call's counter word with one
+//            64-bit atomic (low half: misses so far, high half: tiles done), then writes the
+//            tile's miss entries from LDS to the global list.  The tile that finds every other
+//            tile done publishes *n_miss and clears the word for the next call.
+// The helper exists so that no worker has the atomic's round trip in front of its row loads
+// (vector memory results return in issue order).
+template <int W, int KPW, int U, int WPB>
+__global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArgs a) {
+    constexpr int kTile = KPW * WPB;
+    __shared__ uint64_t s_src[WPB][KPW];
+    __shared__ uint32_t s_dst[WPB][KPW];
+    __shared__ int64_t  s_mkey[WPB][KPW];
+    __shared__ uint32_t s_mpos[WPB][KPW];
+    __shared__ uint32_t s_wcnt[WPB];
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
     const RowGeom g = a.g;
-    const uint32_t rpi = kWave >> g.lprShift;          // rows per wave load
-    const uint32_t sub = (uint32_t)lane >> g.lprShift;  // which of those rows this lane serves
-    const uint32_t cl  = (uint32_t)lane & (g.LPR - 1);  // chunk of the row this lane moves
 
     for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
-        const uint32_t t    = tile / a.tiles_per_table;
-        const uint32_t lt   = tile - t * a.tiles_per_table;
-        const Table   &tb   = a.tab[t];
-        const uint32_t b    = lt * kBlock + threadIdx.x;
-        const bool     live = b < a.B;
-        const uint32_t pos  = t * a.B + b;             // position in keys/out (< 2^32 checked on host)
+        const uint32_t t  = tile / a.tiles_per_table;
+        const uint32_t lt = tile - t * a.tiles_per_table;
+        if (wave < WPB) {
+            const Table   &tb   = a.tab[t];
+            const uint32_t b    = lt * kTile + wave * KPW + lane;
+            const bool     live = lane < KPW && b < a.B;
+            const uint32_t pos  = t * a.B + b;         // position in keys/out (< 2^32 checked on host)
 
-        const int64_t key  = live ? a.keys[pos] : kEmpty;
-        const bool    want = live && !is_reserved(key);
-        const uint32_t set = want ? set_of(key, tb.S, tb.smask) : 0u;
-        const int      way = probe_wave<W>(tb.K, key, set, want);
-        const bool     hit = way >= 0;
+            const int64_t key  = live ? a.keys[pos] : kEmpty;
+            const bool    want = live && !is_reserved(key);
+            const uint32_t set = want ? set_of(key, tb.S, tb.smask) : 0u;
+            const int      way = probe_wave<W, KPW>(tb.K, key, set, want);
+            const bool     hit = way >= 0;
 
-        // ---- phase 2: count misses
-        const uint64_t missmask = __ballot(live && !hit);
-        const uint32_t wmiss    = (uint32_t)__popcll(missmask);
-        if (lane == 0) s_wcnt[wave] = wmiss;
-
-        // ---- phase 3 (list build): hits of this wave, compacted
-        const uint64_t hitmask = __ballot(hit);
-        const uint32_t nh      = (uint32_t)__popcll(hitmask);
-        if (hit) {
-            const int r = rank_in(hitmask);
-            s_src[wave][r] = (uint64_t)set * W + (uint32_t)way;
-            s_dst[wave][r] = pos;
-        }
-        __syncthreads();
-
-        uint32_t woff = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < kWavesPerWg; ++w) {
-            const uint32_t c = s_wcnt[w];
-            woff += (w < wave) ? c : 0u;
-            total += c;
-        }
-        uint64_t old = 0;
-        if (threadIdx.x == 0)
-            old = __hip_atomic_fetch_add(a.slot, (1ull << 32) | (uint64_t)total, __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-
-        // ---- phase 3 (copy): rows of this wave's hits
-        const float *__restrict__ V = tb.V;
-        for (uint32_t pass = 0; pass < g.passes; ++pass) {
-            const uint32_t chunk = cl + pass * g.LPR;
-            const bool cok = chunk < g.C;
-            for (uint32_t e0 = 0; e0 < nh; e0 += rpi * U) {
-                f32x4 buf[U];
-                uint32_t dpos[U];
-                bool ok[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t e = e0 + u * rpi + sub;
-                    ok[u] = cok && e < nh;
-                    if (ok[u]) {
-                        const uint64_t src = s_src[wave][e];
-                        dpos[u] = s_dst[wave][e];
-                        buf[u] = *reinterpret_cast<const f32x4 *>(V + src * g.d + chunk * 4);
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (ok[u])
-                        __builtin_nontemporal_store(
-                            buf[u], reinterpret_cast<f32x4 *>(a.out + (uint64_t)dpos[u] * g.d + chunk * 4));
+            const uint64_t missmask = __ballot(live && !hit);
+            if (live && !hit) {
+                const int r = rank_in(missmask);
+                s_mpos[wave][r] = pos;
+                s_mkey[wave][r] = key;
             }
-        }
+            if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(missmask);
 
-        // ---- phase 2 (write): miss list entries of this tile
-        if (threadIdx.x == 0) {
-            s_base = (uint32_t)old;
-            if ((uint32_t)(old >> 32) + 1u == a.n_tiles) {          // every tile has added its count
+            const uint64_t hitmask = __ballot(hit);
+            const uint32_t nh      = (uint32_t)__popcll(hitmask);
+            if (hit) {
+                const int r = rank_in(hitmask);
+                s_src[wave][r] = (uint64_t)set * W + (uint32_t)way;
+                s_dst[wave][r] = pos;
+            }
+            __syncthreads();
+            if (nh) copy_rows<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
+        } else {
+            __syncthreads();
+            uint32_t total = 0;
+#pragma unroll
+            for (int w = 0; w < WPB; ++w) total += s_wcnt[w];
+            uint64_t old = 0;
+            if (lane == 0)
+                old = __hip_atomic_fetch_add(a.slot, (1ull << 32) | (uint64_t)total, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+            old = (uint64_t)shfl64((int64_t)old, 0);
+            uint32_t o = (uint32_t)old;
+#pragma unroll
+            for (int w = 0; w < WPB; ++w) {
+                const uint32_t c = s_wcnt[w];
+                for (uint32_t j = (uint32_t)lane; j < c; j += kWave) {
+                    a.miss_idx[o + j]  = s_mpos[w][j];
+                    a.miss_keys[o + j] = s_mkey[w][j];
+                }
+                o += c;
+            }
+            if (lane == 0 && (uint32_t)(old >> 32) + 1u == a.n_tiles) {   // every tile has added its count
                 *a.n_miss = (uint32_t)old + total;
                 __hip_atomic_store(a.slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        __syncthreads();
-        if (live && !hit) {
-            const uint32_t o = s_base + woff + (uint32_t)rank_in(missmask);
-            a.miss_idx[o]  = pos;
-            a.miss_keys[o] = key;
-        }
+        __syncthreads();                                // LDS lists are reused by the next tile
     }
 }
 
@@ -296,9 +323,6 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
     const int wave = (int)(threadIdx.x / kWave);
     const RowGeom g = a.g;
     const Table tb = a.tab;
-    const uint32_t rpi = kWave >> g.lprShift;
-    const uint32_t sub = (uint32_t)lane >> g.lprShift;
-    const uint32_t cl  = (uint32_t)lane & (g.LPR - 1);
     uint32_t n = a.n;
     if (a.n_dev) {
         const uint32_t nd = *a.n_dev;
@@ -350,17 +374,8 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
                     s_srcrow[wave][r] = i;
                 }
                 wave_lds_fence();
-                const uint32_t nw = (uint32_t)__popcll(wonmask);
-                for (uint32_t pass = 0; pass < g.passes; ++pass) {
-                    const uint32_t chunk = cl + pass * g.LPR;
-                    for (uint32_t e = sub; e < nw; e += rpi) {
-                        if (chunk < g.C) {
-                            const f32x4 x = *reinterpret_cast<const f32x4 *>(
-                                a.vals + (uint64_t)s_srcrow[wave][e] * g.d + chunk * 4);
-                            *reinterpret_cast<f32x4 *>(tb.V + s_dst[wave][e] * g.d + chunk * 4) = x;
-                        }
-                    }
-                }
+                copy_rows<4>(g, a.vals, tb.V, &s_srcrow[wave][0], &s_dst[wave][0],
+                             (uint32_t)__popcll(wonmask), false);
                 wave_lds_fence();
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                 if (won) {
@@ -513,21 +528,57 @@ uint64_t *next_slot(hps_cache *c) {
     return c->ring + (c->calls.fetch_add(1, std::memory_order_relaxed) % kRing);
 }
 
-template <int W>
-void launch_query_w(const QueryArgs &a, uint32_t grid, hipStream_t st) {
-    hipLaunchKernelGGL((query_kernel<W, 8>), dim3(grid), dim3(kBlock), 0, st, a);
+// Launch shape of the query kernel: KPW keys per wave, U wave loads in flight, WPB waves per
+// work-group.  The default suits a batch of ~10^5 keys on 256 CUs; HPS_QUERY_SHAPE="KPW,U,WPB"
+// in the environment picks another compiled shape for W = 8 (a tuning aid).
+struct QueryShape { int kpw, u, wpb; };
+
+QueryShape query_shape() {
+    static const QueryShape shape = [] {
+        QueryShape q{64, 8, 4};
+        if (const char *e = std::getenv("HPS_QUERY_SHAPE")) {
+            int k = 0, u = 0, w = 0;
+            if (std::sscanf(e, "%d,%d,%d", &k, &u, &w) == 3) q = QueryShape{k, u, w};
+        }
+        return q;
+    }();
+    return shape;
+}
+
+template <int W, int KPW, int U, int WPB>
+void launch_query_shape(const QueryArgs &a, hipStream_t st) {
+    const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
+    hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
+}
+
+uint32_t query_tile(uint32_t W) {          // positions per tile for the shape launch_query will use
+    const QueryShape q = query_shape();
+    return W == 8 ? (uint32_t)(q.kpw * q.wpb) : 256u;
 }
 
 hps_status_t launch_query(uint32_t W, const QueryArgs &a, hipStream_t st) {
-    const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
+    const QueryShape q = query_shape();
     switch (W) {
-        case 1:  launch_query_w<1>(a, grid, st); break;
-        case 2:  launch_query_w<2>(a, grid, st); break;
-        case 4:  launch_query_w<4>(a, grid, st); break;
-        case 8:  launch_query_w<8>(a, grid, st); break;
-        case 16: launch_query_w<16>(a, grid, st); break;
-        case 32: launch_query_w<32>(a, grid, st); break;
-        case 64: launch_query_w<64>(a, grid, st); break;
+        case 1:  launch_query_shape<1, 64, 8, 4>(a, st); break;
+        case 2:  launch_query_shape<2, 64, 8, 4>(a, st); break;
+        case 4:  launch_query_shape<4, 64, 8, 4>(a, st); break;
+        case 16: launch_query_shape<16, 64, 8, 4>(a, st); break;
+        case 32: launch_query_shape<32, 64, 8, 4>(a, st); break;
+        case 64: launch_query_shape<64, 64, 8, 4>(a, st); break;
+        case 8: {
+            const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
+            switch (id) {
+#define HPS_SHAPE(k, u, w) case k * 10000 + u * 100 + w: launch_query_shape<8, k, u, w>(a, st); break;
+                HPS_SHAPE(64, 8, 4) HPS_SHAPE(64, 16, 4) HPS_SHAPE(64, 4, 4) HPS_SHAPE(64, 2, 4)
+                HPS_SHAPE(64, 8, 1) HPS_SHAPE(64, 8, 2) HPS_SHAPE(64, 4, 2) HPS_SHAPE(64, 4, 8) HPS_SHAPE(64, 8, 8)
+                HPS_SHAPE(32, 8, 4) HPS_SHAPE(32, 4, 4) HPS_SHAPE(32, 4, 8) HPS_SHAPE(32, 8, 8)
+                HPS_SHAPE(16, 8, 4) HPS_SHAPE(16, 4, 4) HPS_SHAPE(16, 8, 8) HPS_SHAPE(16, 4, 8)
+                HPS_SHAPE(32, 16, 8) HPS_SHAPE(32, 8, 2) HPS_SHAPE(16, 8, 15) HPS_SHAPE(32, 8, 15)
+#undef HPS_SHAPE
+                default: return fail(HPS_ERR_INVALID_ARG, "HPS_QUERY_SHAPE names a shape that is not compiled in");
+            }
+            break;
+        }
         default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
     }
     HIP_TRY(hipGetLastError());
@@ -688,7 +739,8 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     a.n_miss = n_miss;
     a.slot = next_slot(caches[0]);
     a.B = (uint32_t)batch;
-    a.tiles_per_table = (uint32_t)((batch + kBlock - 1) / kBlock);
+    const uint32_t tile = query_tile(caches[0]->W);
+    a.tiles_per_table = (uint32_t)((batch + tile - 1) / tile);
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
     a.g = make_geom(caches[0]->d);
