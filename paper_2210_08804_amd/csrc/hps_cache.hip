@@ -161,6 +161,59 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
     }
 }
 
+// copy_rows for a reader that may overlap writers (seqlock read side).  Entry e also carries
+// the set it came from and the value v1 of that set's sequence word read before the probe.
+// Rows are loaded into registers, then the sequence words are read again behind an acquire
+// fence; a row is stored only if its word is unchanged, i.e. no writer touched the set while
+// the row was being read.  Returns (through LDS word pair `retry`) the entries to redo.
+template <int U>
+__device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *__restrict__ src,
+                                                  float *__restrict__ dst, const uint64_t *srcRow,
+                                                  const uint32_t *dstRow, const uint32_t *setOf,
+                                                  const uint32_t *v1Of, const uint32_t *seq,
+                                                  uint32_t cnt, uint32_t *retry) {
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t rpi = (uint32_t)kWave >> g.lprShift;
+    const uint32_t sub = lane >> g.lprShift;
+    const uint32_t cl  = lane & (g.LPR - 1);
+    for (uint32_t pass = 0; pass < g.passes; ++pass) {
+        uint32_t chunk = cl + pass * g.LPR;
+        chunk = chunk < g.C ? chunk : 0u;
+        const uint32_t off = chunk * 4;
+        for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
+            f32x4 buf[U];
+            uint32_t ent[U];
+            bool real[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t e = e0 + u * rpi + sub;
+                real[u] = e < cnt;
+                ent[u] = real[u] ? e : 0u;
+                buf[u] = *reinterpret_cast<const f32x4 *>(src + srcRow[ent[u]] * g.d + off);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // row loads complete before the re-read
+            uint32_t v2[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v2[u] = ld_agent(seq + setOf[ent[u]]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // One verdict per row: every lane of the row's group must have seen the unchanged
+                // word (the ballot makes the lanes of a group agree even if their loads did not).
+                const uint64_t bad = __ballot(v2[u] != v1Of[ent[u]]);
+                const uint64_t grp = (g.LPR == 64 ? ~0ull : ((1ull << g.LPR) - 1)) << (sub << g.lprShift);
+                const bool ok = (bad & grp) == 0;
+                if (real[u] && ok) {
+                    __builtin_nontemporal_store(
+                        buf[u], reinterpret_cast<f32x4 *>(dst + (uint64_t)dstRow[ent[u]] * g.d + off));
+                } else if (real[u] && cl == 0) {
+                    __hip_atomic_fetch_or(retry + (ent[u] >> 5), 1u << (ent[u] & 31), __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+        }
+    }
+}
+
 // Set probe for the first KPW lanes' keys of a wave (Alg. 2 "warpReadOutSlab" + match): W lanes
 // read the W slot keys of one set (contiguous 8*W bytes), so one wave load covers 64/W sets; a
 // ballot over the equality test gives every key its way.  Returns the way or -1.
@@ -221,7 +274,13 @@ struct QueryArgs {
 //            tile done publishes *n_miss and clears the word for the next call.
 // The helper exists so that no worker has the atomic's round trip in front of its row loads
 // (vector memory results return in issue order).
-template <int W, int KPW, int U, int WPB>
+//
+// kCoherent = true is the variant for queries that may overlap insert/update kernels on other
+// streams: each worker reads its sets' sequence words before probing, skips sets a writer holds
+// (odd word), copies rows with copy_rows_checked and repeats for the keys whose set changed under
+// it.  A miss needs no check (an 8-byte key is read whole, and a key that stays cached is never
+// absent from its slot), so only hits are validated.
+template <int W, int KPW, int U, int WPB, bool kCoherent>
 __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArgs a) {
     constexpr int kTile = KPW * WPB;
     __shared__ uint64_t s_src[WPB][KPW];
@@ -229,6 +288,9 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
     __shared__ int64_t  s_mkey[WPB][KPW];
     __shared__ uint32_t s_mpos[WPB][KPW];
     __shared__ uint32_t s_wcnt[WPB];
+    __shared__ uint32_t s_set[kCoherent ? WPB : 1][kCoherent ? KPW : 1];
+    __shared__ uint32_t s_v1[kCoherent ? WPB : 1][kCoherent ? KPW : 1];
+    __shared__ uint32_t s_retry[kCoherent ? WPB : 1][2];
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
@@ -246,8 +308,46 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
             const int64_t key  = live ? a.keys[pos] : kEmpty;
             const bool    want = live && !is_reserved(key);
             const uint32_t set = want ? set_of(key, tb.S, tb.smask) : 0u;
-            const int      way = probe_wave<W, KPW>(tb.K, key, set, want);
-            const bool     hit = way >= 0;
+            bool hit;
+            int  way;
+            if (kCoherent) {
+                hit = false;
+                way = -1;
+                bool pending = want;
+                while (__ballot(pending)) {
+                    const uint32_t v1 = pending ? ld_agent(tb.seq + set) : 0u;
+                    const bool busy = pending && (v1 & 1u);          // a writer holds the set: look again later
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    const int w = probe_wave<W, KPW>(tb.K, key, set, pending && !busy);
+                    const bool found = w >= 0;
+                    const uint64_t fmask = __ballot(found);
+                    if (lane < 2) s_retry[wave][lane] = 0u;
+                    if (found) {
+                        const int r = rank_in(fmask);
+                        s_src[wave][r] = (uint64_t)set * W + (uint32_t)w;
+                        s_dst[wave][r] = pos;
+                        s_set[wave][r] = set;
+                        s_v1[wave][r]  = v1;
+                    }
+                    wave_lds_fence();
+                    if (fmask)
+                        copy_rows_checked<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], &s_set[wave][0],
+                                             &s_v1[wave][0], tb.seq, (uint32_t)__popcll(fmask), &s_retry[wave][0]);
+                    wave_lds_fence();
+                    bool again = false;
+                    if (found) {
+                        const int r = rank_in(fmask);
+                        again = (s_retry[wave][r >> 5] >> (r & 31)) & 1u;
+                        if (!again) { hit = true; way = w; }
+                    }
+                    pending = busy || again;                         // a clean miss is final
+                    wave_lds_fence();
+                    if (__ballot(pending)) __builtin_amdgcn_s_sleep(2);
+                }
+            } else {
+                way = probe_wave<W, KPW>(tb.K, key, set, want);
+                hit = way >= 0;
+            }
 
             const uint64_t missmask = __ballot(live && !hit);
             if (live && !hit) {
@@ -257,15 +357,19 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
             }
             if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(missmask);
 
-            const uint64_t hitmask = __ballot(hit);
-            const uint32_t nh      = (uint32_t)__popcll(hitmask);
-            if (hit) {
-                const int r = rank_in(hitmask);
-                s_src[wave][r] = (uint64_t)set * W + (uint32_t)way;
-                s_dst[wave][r] = pos;
+            if (kCoherent) {
+                __syncthreads();                           // rows were copied inside the retry loop
+            } else {
+                const uint64_t hitmask = __ballot(hit);
+                const uint32_t nh      = (uint32_t)__popcll(hitmask);
+                if (hit) {
+                    const int r = rank_in(hitmask);
+                    s_src[wave][r] = (uint64_t)set * W + (uint32_t)way;
+                    s_dst[wave][r] = pos;
+                }
+                __syncthreads();
+                if (nh) copy_rows<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
             }
-            __syncthreads();
-            if (nh) copy_rows<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
         } else {
             __syncthreads();
             uint32_t total = 0;
@@ -546,9 +650,11 @@ QueryShape query_shape() {
 }
 
 template <int W, int KPW, int U, int WPB>
-void launch_query_shape(const QueryArgs &a, hipStream_t st) {
+void launch_query_shape(const QueryArgs &a, bool coherent, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
-    hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
+    const dim3 block((WPB + 1) * kWave);
+    if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 4, WPB, true>), dim3(grid), block, 0, st, a);
+    else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false>), dim3(grid), block, 0, st, a);
 }
 
 uint32_t query_tile(uint32_t W) {          // positions per tile for the shape launch_query will use
@@ -556,24 +662,21 @@ uint32_t query_tile(uint32_t W) {          // positions per tile for the shape l
     return W == 8 ? (uint32_t)(q.kpw * q.wpb) : 256u;
 }
 
-hps_status_t launch_query(uint32_t W, const QueryArgs &a, hipStream_t st) {
+hps_status_t launch_query(uint32_t W, const QueryArgs &a, bool coherent, hipStream_t st) {
     const QueryShape q = query_shape();
     switch (W) {
-        case 1:  launch_query_shape<1, 64, 8, 4>(a, st); break;
-        case 2:  launch_query_shape<2, 64, 8, 4>(a, st); break;
-        case 4:  launch_query_shape<4, 64, 8, 4>(a, st); break;
-        case 16: launch_query_shape<16, 64, 8, 4>(a, st); break;
-        case 32: launch_query_shape<32, 64, 8, 4>(a, st); break;
-        case 64: launch_query_shape<64, 64, 8, 4>(a, st); break;
+        case 1:  launch_query_shape<1, 64, 8, 4>(a, coherent, st); break;
+        case 2:  launch_query_shape<2, 64, 8, 4>(a, coherent, st); break;
+        case 4:  launch_query_shape<4, 64, 8, 4>(a, coherent, st); break;
+        case 16: launch_query_shape<16, 64, 8, 4>(a, coherent, st); break;
+        case 32: launch_query_shape<32, 64, 8, 4>(a, coherent, st); break;
+        case 64: launch_query_shape<64, 64, 8, 4>(a, coherent, st); break;
         case 8: {
             const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
             switch (id) {
-#define HPS_SHAPE(k, u, w) case k * 10000 + u * 100 + w: launch_query_shape<8, k, u, w>(a, st); break;
-                HPS_SHAPE(64, 8, 4) HPS_SHAPE(64, 16, 4) HPS_SHAPE(64, 4, 4) HPS_SHAPE(64, 2, 4)
-                HPS_SHAPE(64, 8, 1) HPS_SHAPE(64, 8, 2) HPS_SHAPE(64, 4, 2) HPS_SHAPE(64, 4, 8) HPS_SHAPE(64, 8, 8)
-                HPS_SHAPE(32, 8, 4) HPS_SHAPE(32, 4, 4) HPS_SHAPE(32, 4, 8) HPS_SHAPE(32, 8, 8)
-                HPS_SHAPE(16, 8, 4) HPS_SHAPE(16, 4, 4) HPS_SHAPE(16, 8, 8) HPS_SHAPE(16, 4, 8)
-                HPS_SHAPE(32, 16, 8) HPS_SHAPE(32, 8, 2) HPS_SHAPE(16, 8, 15) HPS_SHAPE(32, 8, 15)
+#define HPS_SHAPE(k, u, w) case k * 10000 + u * 100 + w: launch_query_shape<8, k, u, w>(a, coherent, st); break;
+                HPS_SHAPE(64, 8, 4) HPS_SHAPE(64, 4, 4) HPS_SHAPE(64, 4, 8) HPS_SHAPE(64, 8, 8)
+                HPS_SHAPE(32, 8, 4) HPS_SHAPE(32, 4, 8) HPS_SHAPE(32, 8, 15) HPS_SHAPE(16, 4, 8)
 #undef HPS_SHAPE
                 default: return fail(HPS_ERR_INVALID_ARG, "HPS_QUERY_SHAPE names a shape that is not compiled in");
             }
@@ -744,7 +847,9 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
     a.g = make_geom(caches[0]->d);
-    return launch_query(caches[0]->W, a, static_cast<hipStream_t>(stream));
+    bool coherent = false;                      // any table that may see concurrent writers makes the call careful
+    for (uint32_t t = 0; t < n_tables; ++t) coherent = coherent || caches[t]->concurrent_writers.load() != 0;
+    return launch_query(caches[0]->W, a, coherent, static_cast<hipStream_t>(stream));
 }
 
 hps_status_t hps_cache_query(hps_cache_t *c, const int64_t *keys, size_t n, float *out,

@@ -23,13 +23,18 @@ def dev(a, dtype=None):
     return t.cuda()
 
 
+CONCURRENT_WRITERS = True      # which query variant new DeviceCache objects use (tests flip it)
+
+
 class DeviceCache:
     """numpy in / numpy out wrapper over the C ABI (one cache)."""
 
-    def __init__(self, capacity, ways, dim):
+    def __init__(self, capacity, ways, dim, concurrent_writers=None):
         self.h = B.hps_cache_create(capacity, ways, dim)
         self.S, self.W, self.d = B.hps_cache_info(self.h)
         assert self.S * self.W == capacity and self.W == ways and self.d == dim
+        cw = CONCURRENT_WRITERS if concurrent_writers is None else concurrent_writers
+        B.hps_cache_set_concurrent_writers(self.h, cw)
 
     def close(self):
         if self.h:

@@ -21,6 +21,16 @@ from harness import (DeviceCache, EMPTY_KEY, RESERVED_KEY, SENTINEL, assert_same
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["checked", "plain"])
+def query_variant(request):
+    """Every test runs against both query kernels: the one that validates rows against
+    concurrent writers (the default) and the plain one for query-only phases."""
+    import harness
+    harness.CONCURRENT_WRITERS = request.param == "checked"
+    yield request.param
+    harness.CONCURRENT_WRITERS = True
+
+
 def rows_u32(keys, d, version=0):
     return inputs.backing_rows(keys, d, version).view(np.uint32)
 
