@@ -95,6 +95,47 @@ template <typename T> __device__ __forceinline__ void st_agent(T *p, T v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Data that kernels overlapping on different streams share (keys, rows, counters of the cache)
+// is accessed in one of two ways, chosen at compile time:
+//   HPS_SCOPED_ACCESS = 1 (default): every such load/store is itself an agent-scope relaxed
+//     atomic of 4 or 8 bytes (the hardware then bypasses non-coherent cache copies), and the
+//     order "sequence word, then data, then sequence word" is kept by waiting until the wave's
+//     outstanding vector memory operations have completed (s_waitcnt vmcnt(0)) between the steps.
+//   HPS_SCOPED_ACCESS = 0: plain accesses between agent-scope acquire/release fences, which
+//     invalidate / write back whole caches and cost several times more.
+#ifndef HPS_SCOPED_ACCESS
+#define HPS_SCOPED_ACCESS 1
+#endif
+
+__device__ __forceinline__ void shared_acquire() {
+#if HPS_SCOPED_ACCESS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#else
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
+}
+__device__ __forceinline__ void shared_release() {
+#if HPS_SCOPED_ACCESS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#else
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+#endif
+}
+__device__ __forceinline__ uint64_t shared_ld64(const uint64_t *p) {
+#if HPS_SCOPED_ACCESS
+    return ld_agent(p);
+#else
+    return *p;
+#endif
+}
+__device__ __forceinline__ void shared_st64(uint64_t *p, uint64_t v) {
+#if HPS_SCOPED_ACCESS
+    st_agent(p, v);
+#else
+    *p = v;
+#endif
+}
+
 struct Table {                 // one cache as the kernels see it
     int64_t  *K;
     float    *V;
@@ -112,6 +153,8 @@ struct RowGeom {
     uint32_t LPR;              // lanes per row: min(64, next power of two >= C)
     uint32_t lprShift;         // log2(LPR)
     uint32_t passes;           // ceil(C / LPR): > 1 only for rows longer than 1 KiB
+    // the same for 8-byte chunks (paths that move rows with 8-byte scoped accesses)
+    uint32_t C8, LPR8, lpr8Shift, passes8;
 };
 
 // Copy `cnt` (> 0) rows listed in LDS: row srcRow[e] of `src` to row dstRow[e] of `dst`, for
@@ -163,9 +206,10 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
 
 // copy_rows for a reader that may overlap writers (seqlock read side).  Entry e also carries
 // the set it came from and the value v1 of that set's sequence word read before the probe.
-// Rows are loaded into registers, then the sequence words are read again behind an acquire
-// fence; a row is stored only if its word is unchanged, i.e. no writer touched the set while
-// the row was being read.  Returns (through LDS word pair `retry`) the entries to redo.
+// Rows are loaded into registers (8 bytes per lane, shared_ld64), then the sequence words are
+// read again once those loads have completed; a row is stored only if its word is unchanged,
+// i.e. no writer touched the set while the row was being read.  Entries to redo are flagged in
+// the LDS word pair `retry`.
 template <int U>
 __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *__restrict__ src,
                                                   float *__restrict__ dst, const uint64_t *srcRow,
@@ -173,15 +217,15 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
                                                   const uint32_t *v1Of, const uint32_t *seq,
                                                   uint32_t cnt, uint32_t *retry) {
     const uint32_t lane = (uint32_t)lane_id();
-    const uint32_t rpi = (uint32_t)kWave >> g.lprShift;
-    const uint32_t sub = lane >> g.lprShift;
-    const uint32_t cl  = lane & (g.LPR - 1);
-    for (uint32_t pass = 0; pass < g.passes; ++pass) {
-        uint32_t chunk = cl + pass * g.LPR;
-        chunk = chunk < g.C ? chunk : 0u;
-        const uint32_t off = chunk * 4;
+    const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;
+    const uint32_t sub = lane >> g.lpr8Shift;
+    const uint32_t cl  = lane & (g.LPR8 - 1);
+    const uint64_t grp = (g.LPR8 == 64 ? ~0ull : ((1ull << g.LPR8) - 1)) << (sub << g.lpr8Shift);
+    for (uint32_t pass = 0; pass < g.passes8; ++pass) {
+        uint32_t chunk = cl + pass * g.LPR8;
+        chunk = chunk < g.C8 ? chunk : 0u;
         for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
-            f32x4 buf[U];
+            uint64_t buf[U];
             uint32_t ent[U];
             bool real[U];
 #pragma unroll
@@ -189,9 +233,9 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
                 const uint32_t e = e0 + u * rpi + sub;
                 real[u] = e < cnt;
                 ent[u] = real[u] ? e : 0u;
-                buf[u] = *reinterpret_cast<const f32x4 *>(src + srcRow[ent[u]] * g.d + off);
+                buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[ent[u]] * g.d) + chunk);
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // row loads complete before the re-read
+            shared_acquire();                                       // row loads complete before the re-read
             uint32_t v2[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) v2[u] = ld_agent(seq + setOf[ent[u]]);
@@ -200,11 +244,10 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
                 // One verdict per row: every lane of the row's group must have seen the unchanged
                 // word (the ballot makes the lanes of a group agree even if their loads did not).
                 const uint64_t bad = __ballot(v2[u] != v1Of[ent[u]]);
-                const uint64_t grp = (g.LPR == 64 ? ~0ull : ((1ull << g.LPR) - 1)) << (sub << g.lprShift);
                 const bool ok = (bad & grp) == 0;
                 if (real[u] && ok) {
                     __builtin_nontemporal_store(
-                        buf[u], reinterpret_cast<f32x4 *>(dst + (uint64_t)dstRow[ent[u]] * g.d + off));
+                        buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[ent[u]] * g.d) + chunk);
                 } else if (real[u] && cl == 0) {
                     __hip_atomic_fetch_or(retry + (ent[u] >> 5), 1u << (ent[u] & 31), __ATOMIC_RELAXED,
                                           __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -214,10 +257,39 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
     }
 }
 
+// Writer side: copy `cnt` rows listed in LDS from the caller's batch into the cache with
+// shared_st64 (8 bytes per lane), so that overlapping readers observe them without cache flushes.
+template <int U>
+__device__ __forceinline__ void copy_rows_shared(const RowGeom g, const float *__restrict__ src,
+                                                 float *dst, const uint32_t *srcRow,
+                                                 const uint64_t *dstRow, uint32_t cnt) {
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;
+    const uint32_t sub = lane >> g.lpr8Shift;
+    const uint32_t cl  = lane & (g.LPR8 - 1);
+    for (uint32_t pass = 0; pass < g.passes8; ++pass) {
+        uint32_t chunk = cl + pass * g.LPR8;
+        chunk = chunk < g.C8 ? chunk : 0u;
+        for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
+            uint64_t buf[U];
+            uint32_t ent[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t e = e0 + u * rpi + sub;
+                ent[u] = e < cnt ? e : 0u;
+                buf[u] = *(reinterpret_cast<const uint64_t *>(src + (uint64_t)srcRow[ent[u]] * g.d) + chunk);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                shared_st64(reinterpret_cast<uint64_t *>(dst + dstRow[ent[u]] * g.d) + chunk, buf[u]);
+        }
+    }
+}
+
 // Set probe for the first KPW lanes' keys of a wave (Alg. 2 "warpReadOutSlab" + match): W lanes
 // read the W slot keys of one set (contiguous 8*W bytes), so one wave load covers 64/W sets; a
 // ballot over the equality test gives every key its way.  Returns the way or -1.
-template <int W, int KPW>
+template <int W, int KPW, bool kShared = false>
 __device__ __forceinline__ int probe_wave(const int64_t *__restrict__ K, int64_t key,
                                           uint32_t set, bool want) {
     constexpr int G = kWave / W;                       // keys per wave load
@@ -230,7 +302,8 @@ __device__ __forceinline__ int probe_wave(const int64_t *__restrict__ K, int64_t
     for (int r = 0; r < R; ++r) {
         const int j = r * G + sub;
         const uint32_t sj = (uint32_t)__shfl((int)set, j, kWave);   // 0 for lanes without a key: a valid set
-        sk[r] = K[(uint64_t)sj * W + slot];
+        const int64_t *p = K + (uint64_t)sj * W + slot;
+        sk[r] = kShared ? (int64_t)shared_ld64(reinterpret_cast<const uint64_t *>(p)) : *p;
     }
     int way = -1;
 #pragma unroll
@@ -317,8 +390,8 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 while (__ballot(pending)) {
                     const uint32_t v1 = pending ? ld_agent(tb.seq + set) : 0u;
                     const bool busy = pending && (v1 & 1u);          // a writer holds the set: look again later
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                    const int w = probe_wave<W, KPW>(tb.K, key, set, pending && !busy);
+                    shared_acquire();                                // the word is read before any key or row
+                    const int w = probe_wave<W, KPW, true>(tb.K, key, set, pending && !busy);
                     const bool found = w >= 0;
                     const uint64_t fmask = __ballot(found);
                     if (lane < 2) s_retry[wave][lane] = 0u;
@@ -465,7 +538,7 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
             }
             const uint64_t wonmask = __ballot(won);
             if (wonmask) {
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                shared_acquire();
                 if (won) {
                     if (kInsert) {
                         const uint32_t c = ld_agent(tb.ctr + set);
@@ -478,10 +551,10 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
                     s_srcrow[wave][r] = i;
                 }
                 wave_lds_fence();
-                copy_rows<4>(g, a.vals, tb.V, &s_srcrow[wave][0], &s_dst[wave][0],
-                             (uint32_t)__popcll(wonmask), false);
+                copy_rows_shared<8>(g, a.vals, tb.V, &s_srcrow[wave][0], &s_dst[wave][0],
+                                    (uint32_t)__popcll(wonmask));
                 wave_lds_fence();
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                shared_release();                                    // rows and key land before the word moves on
                 if (won) {
                     st_agent(tb.seq + set, v + 2u);
                     pending = false;
@@ -583,6 +656,12 @@ RowGeom make_geom(uint32_t d) {
     g.LPR = lpr;
     g.lprShift = sh;
     g.passes = (g.C + lpr - 1) / lpr;
+    g.C8 = d / 2;
+    lpr = 1; sh = 0;
+    while (lpr < g.C8 && lpr < (uint32_t)kWave) { lpr <<= 1; ++sh; }
+    g.LPR8 = lpr;
+    g.lpr8Shift = sh;
+    g.passes8 = (g.C8 + lpr - 1) / lpr;
     return g;
 }
 
@@ -653,7 +732,7 @@ template <int W, int KPW, int U, int WPB>
 void launch_query_shape(const QueryArgs &a, bool coherent, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
-    if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 4, WPB, true>), dim3(grid), block, 0, st, a);
+    if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 8, WPB, true>), dim3(grid), block, 0, st, a);
     else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false>), dim3(grid), block, 0, st, a);
 }
 
