@@ -1,0 +1,265 @@
+"""Parity at the full sizes of the workloads, in the launch configuration the benchmark times.
+
+The oracle runs with dim = 1: its one-word row is the version tag of the key's row, and the
+expected fp32 row is the backing generator's row for (key, version).  Neither side mirrors
+gigabytes of rows on the host.  Where the cache state is needed on both sides it is computed by
+the oracle and imported into the GPU cache (keys and counters), after which the rows are filled
+on the GPU by the refresh cycle of Sec. 6: dump keys -> fetch rows from the backing stand-in ->
+update.  Miss lists are compared exactly; rows exactly on all or on sampled positions.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import OracleCache
+from paper_2210_08804_amd import binding as B
+from paper_2210_08804_amd import inputs
+from harness import DeviceCache, SENTINEL, EMPTY_KEY, canonical
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_prefill_descending(oc, n_ids, chunk):
+    tags = np.zeros((chunk, 1), dtype=np.uint32)
+    for hi in range(n_ids, 0, -chunk):
+        lo = max(0, hi - chunk)
+        oc.insert(np.arange(hi - 1, lo - 1, -1, dtype=np.int64), tags[: hi - lo])
+
+
+def refresh_cycle(gc, version, slots_per_batch):
+    """Sec. 6 steps 2-5 on the device: dump a slot range, fetch the rows, update the cache."""
+    total = gc.S * gc.W
+    keys = torch.empty(slots_per_batch, dtype=torch.int64, device="cuda")
+    rows = torch.empty(slots_per_batch, gc.d, dtype=torch.float32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dumped = 0
+    for first in range(0, total, slots_per_batch):
+        m = min(slots_per_batch, total - first)
+        B.hps_cache_dump(gc.h, first, m, keys, cnt)
+        B.hps_backing_fetch(keys, m, gc.d, version=version, rows=rows, n_dev=cnt)
+        B.hps_cache_update_dn(gc.h, keys, rows, m, cnt)
+        dumped += int(cnt.item())
+    torch.cuda.synchronize()
+    return dumped
+
+
+def gpu_query(gc, dkeys, n):
+    out = torch.full((n, gc.d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32)
+    mi = torch.empty(n, dtype=torch.int32, device="cuda")
+    mk = torch.empty(n, dtype=torch.int64, device="cuda")
+    nm = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.hps_cache_query(gc.h, dkeys, n, out, mi, mk, nm)
+    torch.cuda.synchronize()
+    m = int(nm.item())
+    order = torch.argsort(mi[:m].to(torch.int64) & 0xFFFFFFFF)
+    return out, mi[:m][order].cpu().numpy().view(np.uint32), mk[:m][order].cpu().numpy()
+
+
+def check_rows(out, keys, tags_hit_mask, versions, sample=None):
+    """out: device [n, d] fp32; rows of hit positions must equal backing_rows(key, version)."""
+    n, d = out.shape
+    idx = np.arange(n) if sample is None else sample
+    got = out[torch.from_numpy(idx).cuda()].view(torch.int32).cpu().numpy().view(np.uint32)
+    hit = tags_hit_mask[idx]
+    exp = inputs.backing_rows(keys[idx], d, versions[idx]).view(np.uint32)
+    assert (got[hit] == exp[hit]).all(), "a hit row differs from the row of its key and version"
+    assert (got[~hit] == SENTINEL).all(), "a miss row was written"
+
+
+@pytest.mark.parametrize("mode", ["plain", "checked"])
+def test_c2_hot_cache_query_full_size(mode):
+    S, W, d = 1 << 21, 8, 128
+    n = 4096 * 26
+    oc = OracleCache(S * W, W, 1)
+    oracle_prefill_descending(oc, S * W, 1 << 18)
+    occupied = int((np.array(oc.keys) != EMPTY_KEY).sum())
+    assert 0.84 < occupied / (S * W) < 0.88            # Poisson(8) loads truncated at 8 ways: about 0.86
+    with DeviceCache(S * W, W, d, concurrent_writers=(mode == "checked")) as gc:
+        gc.load(np.array(oc.keys), np.array(oc.ctr))
+        assert refresh_cycle(gc, 0, 1 << 22) == occupied
+        for seed in (1, 2, 500, 1000):
+            keys = inputs.zipf_keys(n, 10 ** 8, 1.05, seed)
+            tags = np.full((n, 1), 0xFFFFFFFF, dtype=np.uint32)
+            _, omi, omk = oc.query(keys, tags)
+            out, gmi, gmk = gpu_query(gc, torch.from_numpy(keys).cuda(), n)
+            assert len(gmi) == len(omi) and (gmi == omi).all() and (gmk == omk).all()
+            hit = tags[:, 0] != 0xFFFFFFFF
+            assert 0.90 < hit.mean() < 0.96
+            check_rows(out, keys, hit, np.zeros(n, dtype=np.int64))
+    oc.close()
+
+
+def test_c3_streaming_query_and_miss_fill_full_size():
+    """Per step: query -> fetch the missing rows from the backing stand-in on the device ->
+    insert them (Alg. 1, synchronous branch).  Both sides run every step; the canonical states
+    (keys and counters per set) are compared after every insert."""
+    S, W, d = 1 << 20, 8, 128
+    n = 16384 * 26
+    steps = 40
+    oc = OracleCache(S * W, W, 1)
+    hit_rates = []
+    with DeviceCache(S * W, W, d, concurrent_writers=False) as gc:
+        rows = torch.empty(n, d, dtype=torch.float32, device="cuda")
+        for step in range(1, steps + 1):
+            keys = inputs.zipf_keys(n, 10 ** 8, 1.1, step)
+            dk = torch.from_numpy(keys).cuda()
+            out = torch.full((n, d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32)
+            mi = torch.empty(n, dtype=torch.int32, device="cuda")
+            mk = torch.empty(n, dtype=torch.int64, device="cuda")
+            nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+            B.hps_cache_query(gc.h, dk, n, out, mi, mk, nm)
+            B.hps_backing_fetch(mk, n, d, version=0, rows=rows, n_dev=nm, scatter_idx=mi, scatter_out=out)
+            B.hps_cache_insert_dn(gc.h, mk, rows, n, nm)
+            torch.cuda.synchronize()
+            m = int(nm.item())
+            tags = np.full((n, 1), 0xFFFFFFFF, dtype=np.uint32)
+            _, omi, omk = oc.query(keys, tags)
+            order = np.argsort(mi[:m].cpu().numpy().view(np.uint32))
+            assert m == len(omi)
+            assert (mi[:m].cpu().numpy().view(np.uint32)[order] == omi).all()
+            assert (mk[:m].cpu().numpy()[order] == omk).all()
+            hit_rates.append(1.0 - m / n)
+            # after the fill every row of `out` is the row of its key (hits gathered, misses fetched)
+            sample = np.random.Generator(np.random.PCG64(step)).choice(n, 4096, replace=False)
+            got = out[torch.from_numpy(sample).cuda()].view(torch.int32).cpu().numpy().view(np.uint32)
+            assert (got == inputs.backing_rows(keys[sample], d, 0).view(np.uint32)).all()
+            oc.insert(omk, np.zeros((m, 1), dtype=np.uint32))
+            gk, gctr, _ = gc.export(with_vals=False)
+            ck, cc, _ = canonical(gk, gctr, None)
+            ok_, occ, _ = canonical(np.array(oc.keys), np.array(oc.ctr), None)
+            assert (cc == occ).all() and (ck == ok_).all(), f"state differs after step {step}"
+            oc.load_state(gk, gctr)            # adopt the GPU's way order of same-batch arrivals
+    assert hit_rates[0] == 0.0 or hit_rates[0] < 0.7
+    assert all(b >= a - 0.02 for a, b in zip(hit_rates, hit_rates[1:])), hit_rates     # warm-up: rising hit rate
+    assert hit_rates[-1] > hit_rates[1]
+    oc.close()
+
+
+def test_c4_multi_table_lookup_one_launch_full_size():
+    W, d, Bn = 8, 128, 131072
+    vocab = inputs.log_uniform_vocab(26, 1e3, 1e8, 7)
+    slots = [int(min(0.2 * v, 1 << 22)) // 8 * 8 for v in vocab]
+    caches, oracles = [], []
+    try:
+        keys = np.empty((26, Bn), dtype=np.int64)
+        for t, (v, s) in enumerate(zip(vocab.tolist(), slots)):
+            oc = OracleCache(s, W, 1)
+            oracle_prefill_descending(oc, s, 1 << 18)          # hottest `slots` ids, hottest last
+            gc = DeviceCache(s, W, d, concurrent_writers=False)
+            gc.load(np.array(oc.keys), np.array(oc.ctr))
+            refresh_cycle(gc, 0, min(s, 1 << 22))
+            caches.append(gc)
+            oracles.append(oc)
+            keys[t] = inputs.zipf_keys(Bn, v, 1.05, 7 + 1000 * t)
+        n = 26 * Bn
+        dk = torch.from_numpy(keys).cuda()
+        out = torch.full((n, d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32)
+        mi = torch.empty(n, dtype=torch.int32, device="cuda")
+        mk = torch.empty(n, dtype=torch.int64, device="cuda")
+        nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.hps_cache_query_multi([c.h for c in caches], dk, Bn, out, mi, mk, nm)
+        torch.cuda.synchronize()
+        m = int(nm.item())
+        order = np.argsort(mi[:m].cpu().numpy().view(np.uint32))
+        gmi = mi[:m].cpu().numpy().view(np.uint32)[order]
+        gmk = mk[:m].cpu().numpy()[order]
+        emi, emk, hit = [], [], np.zeros(n, dtype=bool)
+        for t, oc in enumerate(oracles):
+            tags = np.full((Bn, 1), 0xFFFFFFFF, dtype=np.uint32)
+            _, omi, omk = oc.query(keys[t], tags)
+            emi.append(omi.astype(np.int64) + t * Bn)
+            emk.append(omk)
+            hit[t * Bn:(t + 1) * Bn] = tags[:, 0] != 0xFFFFFFFF
+        emi, emk = np.concatenate(emi), np.concatenate(emk)
+        assert m == len(emi) and (gmi == emi).all() and (gmk == emk).all()
+        sample = np.random.Generator(np.random.PCG64(4)).choice(n, 60000, replace=False)
+        check_rows(out, keys.reshape(-1), hit, np.zeros(n, dtype=np.int64), sample=np.sort(sample))
+    finally:
+        for c in caches:
+            c.close()
+        for o in oracles:
+            o.close()
+
+
+def test_c5_online_update_concurrent_with_query_full_size():
+    """64 GiB cache (2^24 sets x 8 ways x 128 fp32).  Query batches of 65,536 x 26 Zipf keys on
+    one stream, update batches of 262,144 <key, row> pairs (half of the keys resident) on a
+    second stream.  Every hit must carry the complete row of one version of its key; versions
+    seen never go backwards from one query to the next; hit/miss sets equal the oracle's (update
+    never changes residency); after both streams are drained a re-query equals the oracle."""
+    S, W, d = 1 << 24, 8, 128
+    n_q, n_u, rounds = 65536 * 26, 262144, 6
+    oc = OracleCache(S * W, W, 1)
+    oracle_prefill_descending(oc, S * W, 1 << 20)
+    rng = np.random.Generator(np.random.PCG64(5))
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        gc.load(np.array(oc.keys), np.array(oc.ctr))
+        occupied = int((np.array(oc.keys) != EMPTY_KEY).sum())
+        assert refresh_cycle(gc, 0, 1 << 24) == occupied
+
+        q_keys = [inputs.zipf_keys(n_q, 10 ** 9, 1.05, 100 + r) for r in range(rounds)]
+        upd_keys = []
+        for r in range(rounds):
+            cand = np.unique(np.concatenate([q_keys[r][: n_u], rng.integers(0, S * W, n_u)]))
+            tags = np.full((len(cand), 1), 0xFFFFFFFF, dtype=np.uint32)
+            oc.query(cand, tags)
+            res = cand[tags[:, 0] != 0xFFFFFFFF]
+            res = rng.permutation(res)[: n_u // 2]
+            absent = rng.integers(2 * 10 ** 9, 3 * 10 ** 9, n_u - len(res))
+            upd_keys.append(rng.permutation(np.concatenate([res, absent])).astype(np.int64))
+        qs, us = torch.cuda.Stream(), torch.cuda.Stream()
+        d_q = [torch.from_numpy(k).cuda() for k in q_keys]
+        d_u = [torch.from_numpy(k).cuda() for k in upd_keys]
+        d_urows = [torch.empty(n_u, d, dtype=torch.float32, device="cuda") for _ in range(rounds)]
+        for r in range(rounds):
+            B.hps_backing_fetch(d_u[r], n_u, d, version=r + 1, rows=d_urows[r])
+        outs = [torch.full((n_q, d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32) for _ in range(rounds)]
+        mi = [torch.empty(n_q, dtype=torch.int32, device="cuda") for _ in range(rounds)]
+        mk = [torch.empty(n_q, dtype=torch.int64, device="cuda") for _ in range(rounds)]
+        nm = torch.zeros(rounds, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        for r in range(rounds):
+            B.hps_cache_query(gc.h, d_q[r], n_q, outs[r], mi[r], mk[r], nm[r:r + 1], qs)
+            B.hps_cache_update(gc.h, d_u[r], d_urows[r], n_u, us)
+        torch.cuda.synchronize()
+
+        last = {}
+        for r in range(rounds):
+            m = int(nm[r].item())
+            tags = np.full((n_q, 1), 0xFFFFFFFF, dtype=np.uint32)
+            _, omi, omk = oc.query(q_keys[r], tags)
+            order = np.argsort(mi[r][:m].cpu().numpy().view(np.uint32))
+            assert m == len(omi) and (mi[r][:m].cpu().numpy().view(np.uint32)[order] == omi).all()
+            assert (mk[r][:m].cpu().numpy()[order] == omk).all()
+            hit = tags[:, 0] != 0xFFFFFFFF
+            # sample: every position whose key is in some update batch (first 30000) + random ones
+            in_upd = np.isin(q_keys[r], np.concatenate(upd_keys))
+            sample = np.unique(np.concatenate([np.nonzero(in_upd)[0][:30000], rng.choice(n_q, 20000, replace=False)]))
+            got = outs[r][torch.from_numpy(sample).cuda()].view(torch.int32).cpu().numpy().view(np.uint32)
+            ks = q_keys[r][sample]
+            seen = np.full(len(sample), -2, dtype=np.int64)
+            seen[(got == SENTINEL).all(axis=1)] = -1
+            for v in range(rounds + 1):
+                seen[(got == inputs.backing_rows(ks, d, v).view(np.uint32)).all(axis=1)] = v
+            assert (seen != -2).all(), f"round {r}: {(seen == -2).sum()} sampled rows match no single version"
+            assert ((seen == -1) == ~hit[sample]).all()
+            newest = {}
+            for k, v in zip(ks[hit[sample]].tolist(), seen[hit[sample]].tolist()):
+                assert v >= last.get(k, 0), "a later query saw an older version"
+                newest[k] = max(newest.get(k, 0), v)
+            last.update(newest)
+        # drained: the oracle applies the updates in order (tag = version); re-query and compare
+        for r in range(rounds):
+            oc.update(upd_keys[r], np.full((n_u, 1), r + 1, dtype=np.uint32))
+        keys = np.concatenate([np.concatenate(upd_keys)[:: 4], q_keys[0][:200000]])
+        n = len(keys)
+        tags = np.full((n, 1), 0xFFFFFFFF, dtype=np.uint32)
+        _, omi, omk = oc.query(keys, tags)
+        out, gmi, gmk = gpu_query(gc, torch.from_numpy(keys).cuda(), n)
+        assert len(gmi) == len(omi) and (gmi == omi).all() and (gmk == omk).all()
+        hit = tags[:, 0] != 0xFFFFFFFF
+        assert (tags[hit, 0] > 0).sum() > 50000           # plenty of updated rows among them
+        versions = np.where(hit, tags[:, 0], 0).astype(np.int64)
+        sample = np.sort(rng.choice(n, 80000, replace=False))
+        check_rows(out, keys, hit, versions, sample=sample)
+    oc.close()
