@@ -114,6 +114,16 @@ const char *hps_last_error(void);
  */
 hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *cache, int enabled);
 
+/*
+ * Deduplicate the keys of each query tile before the lookup (the paper applies a dedup operator
+ * to every batch before any lookup, Sec. 2.2).  enabled = 1: plain-mode queries
+ * (set_concurrent_writers(0)) elect one representative per distinct key of a 256- or 512-key
+ * tile in LDS, probe and read each distinct row once and fan it out to the duplicate positions.
+ * Results are identical.  Default 0: on MI355X the duplicate reads of a Zipf batch already hit
+ * in L2, and the extra LDS rounds cost more than they save (measured 29 us vs 24 us per batch).
+ */
+hps_status_t hps_cache_set_query_dedup(hps_cache_t *cache, int enabled);
+
 /* Geometry of a cache.  Any output pointer [host] may be NULL. */
 hps_status_t hps_cache_info(const hps_cache_t *cache, uint64_t *num_sets, uint32_t *ways,
                             uint32_t *dim);

@@ -23,7 +23,7 @@ EXPORTS = (
     "hps_cache_create", "hps_cache_destroy", "hps_cache_query", "hps_cache_insert",
     "hps_cache_update", "hps_last_error", "hps_cache_set_concurrent_writers", "hps_cache_info",
     "hps_cache_export", "hps_cache_import", "hps_cache_dump", "hps_cache_query_multi",
-    "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn",
+    "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn", "hps_cache_set_query_dedup",
 )
 
 _lib = None
@@ -55,6 +55,7 @@ def load_library():
         "hps_cache_insert": [vp, vp, vp, sz, vp],
         "hps_cache_update": [vp, vp, vp, sz, vp],
         "hps_cache_set_concurrent_writers": [vp, C.c_int],
+        "hps_cache_set_query_dedup": [vp, C.c_int],
         "hps_cache_info": [vp, C.POINTER(C.c_uint64), C.POINTER(u32), C.POINTER(u32)],
         "hps_cache_export": [vp, vp, vp, vp, vp],
         "hps_cache_import": [vp, vp, vp, vp, vp],
@@ -134,6 +135,10 @@ def hps_cache_update_dn(handle, keys, vals, n_max, n_dev, stream=None) -> None:
 
 def hps_cache_set_concurrent_writers(handle, enabled: bool) -> None:
     _check(load_library().hps_cache_set_concurrent_writers(handle, 1 if enabled else 0))
+
+
+def hps_cache_set_query_dedup(handle, enabled: bool) -> None:
+    _check(load_library().hps_cache_set_query_dedup(handle, 1 if enabled else 0))
 
 
 def hps_cache_info(handle):

@@ -472,6 +472,156 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
     }
 }
 
+// Query with in-tile deduplication (the paper deduplicates a batch before the lookup, Sec. 2.2;
+// here each tile of WPB*64 positions does it in LDS).  An LDS hash table (2 slots per position,
+// 64-bit compare-and-swap, linear probing) elects one representative position per distinct key of
+// the tile.  Only representatives probe the cache and only their rows are read from memory; a
+// row is then stored to the representative's position and to every duplicate position, which
+// hang off the representative in an LDS linked list (atomic exchange on the list head).  Misses
+// are reported per position as in query_kernel, and the helper wave does the same counter work.
+template <int W, int U, int WPB>
+__global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const QueryArgs a) {
+    constexpr int kTile = kWave * WPB;
+    constexpr int kHash = 2 * kTile;
+    constexpr uint32_t kNil = 0xFFFFFFFFu;
+    constexpr uint64_t kMissed = ~0ull;
+    __shared__ unsigned long long h_key[kHash];
+    __shared__ uint32_t h_own[kHash];
+    __shared__ uint64_t r_slot[kTile];
+    __shared__ uint32_t head[kTile];
+    __shared__ uint32_t nxt[kTile];
+    __shared__ uint64_t s_src[WPB][kWave];
+    __shared__ uint32_t s_rep[WPB][kWave];
+    __shared__ int64_t  s_mkey[WPB][kWave];
+    __shared__ uint32_t s_mpos[WPB][kWave];
+    __shared__ uint32_t s_wcnt[WPB];
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    const RowGeom g = a.g;
+    const uint32_t rpi = (uint32_t)kWave >> g.lprShift;
+    const uint32_t sub = (uint32_t)lane >> g.lprShift;
+    const uint32_t cl  = (uint32_t)lane & (g.LPR - 1);
+
+    for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+        const uint32_t t  = tile / a.tiles_per_table;
+        const uint32_t lt = tile - t * a.tiles_per_table;
+        const uint32_t pos0 = t * a.B + lt * kTile;            // position of this tile's first key
+        if (wave < WPB) {
+            const Table   &tb   = a.tab[t];
+            const uint32_t tid  = (uint32_t)threadIdx.x;       // worker threads come first
+            const uint32_t b    = lt * kTile + tid;
+            const bool     live = b < a.B;
+            const uint32_t pos  = pos0 + tid;
+            const int64_t  key  = live ? a.keys[pos] : kEmpty;
+            const bool     want = live && !is_reserved(key);
+            const uint64_t h    = mix64((uint64_t)key);
+            const uint32_t hs   = (uint32_t)(h >> 32);
+            const uint32_t set  = want ? (tb.smask ? (hs & tb.smask) : (hs % tb.S)) : 0u;
+
+            for (uint32_t i = tid; i < (uint32_t)kHash; i += kTile) h_key[i] = (unsigned long long)kEmpty;
+            head[tid] = kNil;
+            __syncthreads();                                    // #1 table cleared
+
+            bool is_rep = false;
+            uint32_t my = 0;
+            if (want) {
+                uint32_t slot = (uint32_t)h & (kHash - 1);
+                for (;;) {
+                    const unsigned long long old =
+                        atomicCAS(&h_key[slot], (unsigned long long)kEmpty, (unsigned long long)key);
+                    if (old == (unsigned long long)kEmpty) { is_rep = true; h_own[slot] = tid; break; }
+                    if (old == (unsigned long long)key) break;
+                    slot = (slot + 1) & (kHash - 1);
+                }
+                my = slot;
+            }
+            __syncthreads();                                    // #2 representatives elected
+            const uint32_t rep = is_rep ? tid : (want ? h_own[my] : tid);
+            const int way = probe_wave<W, kWave>(tb.K, key, set, is_rep);
+            if (is_rep) r_slot[tid] = way >= 0 ? (uint64_t)set * W + (uint32_t)way : kMissed;
+            __syncthreads();                                    // #3 probe results visible
+            const uint64_t res = want ? r_slot[rep] : kMissed;
+            const bool hit = res != kMissed;
+
+            const uint64_t missmask = __ballot(live && !hit);
+            if (live && !hit) {
+                const int r = rank_in(missmask);
+                s_mpos[wave][r] = pos;
+                s_mkey[wave][r] = key;
+            }
+            if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(missmask);
+
+            if (hit && !is_rep) nxt[tid] = atomicExch(&head[rep], tid);     // join the representative's list
+            const uint64_t repmask = __ballot(hit && is_rep);
+            const uint32_t nh = (uint32_t)__popcll(repmask);
+            if (hit && is_rep) {
+                const int r = rank_in(repmask);
+                s_src[wave][r] = res;
+                s_rep[wave][r] = tid;
+            }
+            __syncthreads();                                    // #4 lists complete; helper starts
+
+            const float *__restrict__ V = tb.V;
+            for (uint32_t pass = 0; pass < g.passes; ++pass) {
+                uint32_t chunk = cl + pass * g.LPR;
+                chunk = chunk < g.C ? chunk : 0u;
+                const uint32_t off = chunk * 4;
+                for (uint32_t e0 = 0; e0 < nh; e0 += rpi * U) {
+                    f32x4 buf[U];
+                    uint32_t rp[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        uint32_t e = e0 + u * rpi + sub;
+                        e = e < nh ? e : 0u;
+                        rp[u] = s_rep[wave][e];
+                        buf[u] = *reinterpret_cast<const f32x4 *>(V + s_src[wave][e] * g.d + off);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        __builtin_nontemporal_store(
+                            buf[u], reinterpret_cast<f32x4 *>(a.out + (uint64_t)(pos0 + rp[u]) * g.d + off));
+                        uint32_t p = head[rp[u]];
+                        while (p != kNil) {                     // duplicate positions of this key
+                            __builtin_nontemporal_store(
+                                buf[u], reinterpret_cast<f32x4 *>(a.out + (uint64_t)(pos0 + p) * g.d + off));
+                            p = nxt[p];
+                        }
+                    }
+                }
+            }
+        } else {
+            __syncthreads();
+            __syncthreads();
+            __syncthreads();
+            __syncthreads();
+            uint32_t total = 0;
+#pragma unroll
+            for (int w = 0; w < WPB; ++w) total += s_wcnt[w];
+            uint64_t old = 0;
+            if (lane == 0)
+                old = __hip_atomic_fetch_add(a.slot, (1ull << 32) | (uint64_t)total, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+            old = (uint64_t)shfl64((int64_t)old, 0);
+            uint32_t o = (uint32_t)old;
+#pragma unroll
+            for (int w = 0; w < WPB; ++w) {
+                const uint32_t c = s_wcnt[w];
+                for (uint32_t j = (uint32_t)lane; j < c; j += kWave) {
+                    a.miss_idx[o + j]  = s_mpos[w][j];
+                    a.miss_keys[o + j] = s_mkey[w][j];
+                }
+                o += c;
+            }
+            if (lane == 0 && (uint32_t)(old >> 32) + 1u == a.n_tiles) {
+                *a.n_miss = (uint32_t)old + total;
+                __hip_atomic_store(a.slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();                                        // #5 LDS is reused by the next tile
+    }
+}
+
 // ------------------------------------------------------------------ insert / update
 
 struct WriteArgs {
@@ -681,6 +831,7 @@ struct hps_cache {
     uint64_t *ring;                       // kRing counter words, all zero between calls
     std::atomic<uint32_t> calls;
     std::atomic<int> concurrent_writers;
+    std::atomic<int> query_dedup;
 };
 
 namespace {
@@ -711,60 +862,64 @@ uint64_t *next_slot(hps_cache *c) {
     return c->ring + (c->calls.fetch_add(1, std::memory_order_relaxed) % kRing);
 }
 
-// Launch shape of the query kernel: KPW keys per wave, U wave loads in flight, WPB waves per
-// work-group.  The default suits a batch of ~10^5 keys on 256 CUs; HPS_QUERY_SHAPE="KPW,U,WPB"
-// in the environment picks another compiled shape for W = 8 (a tuning aid).
+// Launch shape of the query kernel: KPW keys per worker wave, U wave loads in flight, WPB worker
+// waves per work-group.  Chosen from the batch size (measured on 256 CUs with 512-byte rows):
+// small batches want many small work-groups, ~10^5 keys want 512-key tiles (half as many
+// same-address counter atomics, which cost ~11 ns each and serialise), large batches want
+// more loads in flight.  HPS_QUERY_SHAPE="KPW,U,WPB" in the environment overrides the choice
+// with another compiled shape (a tuning aid).
 struct QueryShape { int kpw, u, wpb; };
 
-QueryShape query_shape() {
-    static const QueryShape shape = [] {
-        QueryShape q{64, 8, 4};
+QueryShape query_shape(uint64_t n) {
+    static const QueryShape forced = [] {
+        QueryShape q{0, 0, 0};
         if (const char *e = std::getenv("HPS_QUERY_SHAPE")) {
             int k = 0, u = 0, w = 0;
             if (std::sscanf(e, "%d,%d,%d", &k, &u, &w) == 3) q = QueryShape{k, u, w};
         }
         return q;
     }();
-    return shape;
+    if (forced.kpw) return forced;
+    if (n < (1u << 16)) return QueryShape{64, 4, 4};
+    if (n < (1u << 18)) return QueryShape{64, 4, 8};
+    return QueryShape{64, 8, 4};
 }
 
 template <int W, int KPW, int U, int WPB>
-void launch_query_shape(const QueryArgs &a, bool coherent, hipStream_t st) {
+void launch_query_shape(const QueryArgs &a, bool coherent, bool dedup, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
     if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 8, WPB, true>), dim3(grid), block, 0, st, a);
+    else if (dedup && KPW == kWave)
+        hipLaunchKernelGGL((query_dedup_kernel<W, U, WPB>), dim3(grid), block, 0, st, a);
     else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false>), dim3(grid), block, 0, st, a);
 }
 
-uint32_t query_tile(uint32_t W) {          // positions per tile for the shape launch_query will use
-    const QueryShape q = query_shape();
-    return W == 8 ? (uint32_t)(q.kpw * q.wpb) : 256u;
-}
-
-hps_status_t launch_query(uint32_t W, const QueryArgs &a, bool coherent, hipStream_t st) {
-    const QueryShape q = query_shape();
-    switch (W) {
-        case 1:  launch_query_shape<1, 64, 8, 4>(a, coherent, st); break;
-        case 2:  launch_query_shape<2, 64, 8, 4>(a, coherent, st); break;
-        case 4:  launch_query_shape<4, 64, 8, 4>(a, coherent, st); break;
-        case 16: launch_query_shape<16, 64, 8, 4>(a, coherent, st); break;
-        case 32: launch_query_shape<32, 64, 8, 4>(a, coherent, st); break;
-        case 64: launch_query_shape<64, 64, 8, 4>(a, coherent, st); break;
-        case 8: {
-            const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
-            switch (id) {
-#define HPS_SHAPE(k, u, w) case k * 10000 + u * 100 + w: launch_query_shape<8, k, u, w>(a, coherent, st); break;
-                HPS_SHAPE(64, 8, 4) HPS_SHAPE(64, 4, 4) HPS_SHAPE(64, 4, 8) HPS_SHAPE(64, 8, 8)
-                HPS_SHAPE(32, 8, 4) HPS_SHAPE(32, 4, 8) HPS_SHAPE(32, 8, 15) HPS_SHAPE(16, 4, 8)
-#undef HPS_SHAPE
-                default: return fail(HPS_ERR_INVALID_ARG, "HPS_QUERY_SHAPE names a shape that is not compiled in");
-            }
-            break;
-        }
-        default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
+template <int W>
+hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, bool dedup, hipStream_t st) {
+    const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
+    switch (id) {
+        case 640404: launch_query_shape<W, 64, 4, 4>(a, coherent, dedup, st); break;
+        case 640408: launch_query_shape<W, 64, 4, 8>(a, coherent, dedup, st); break;
+        case 640804: launch_query_shape<W, 64, 8, 4>(a, coherent, dedup, st); break;
+        default: return fail(HPS_ERR_INVALID_ARG, "HPS_QUERY_SHAPE names a shape that is not compiled in");
     }
     HIP_TRY(hipGetLastError());
     return HPS_OK;
+}
+
+hps_status_t launch_query(uint32_t W, const QueryArgs &a, QueryShape q, bool coherent, bool dedup,
+                          hipStream_t st) {
+    switch (W) {
+        case 1:  return launch_query_w<1>(a, q, coherent, dedup, st);
+        case 2:  return launch_query_w<2>(a, q, coherent, dedup, st);
+        case 4:  return launch_query_w<4>(a, q, coherent, dedup, st);
+        case 8:  return launch_query_w<8>(a, q, coherent, dedup, st);
+        case 16: return launch_query_w<16>(a, q, coherent, dedup, st);
+        case 32: return launch_query_w<32>(a, q, coherent, dedup, st);
+        case 64: return launch_query_w<64>(a, q, coherent, dedup, st);
+        default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
+    }
 }
 
 template <bool kInsert>
@@ -832,6 +987,7 @@ hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim, hps_
     c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr;
     c->calls.store(0);
     c->concurrent_writers.store(1);
+    c->query_dedup.store(0);
 
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipMalloc(&c->K, capacity * sizeof(int64_t));
@@ -892,6 +1048,12 @@ hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *c, int enabled) {
     return HPS_OK;
 }
 
+hps_status_t hps_cache_set_query_dedup(hps_cache_t *c, int enabled) {
+    if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    c->query_dedup.store(enabled ? 1 : 0);
+    return HPS_OK;
+}
+
 hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables, const int64_t *keys,
                                    size_t batch, float *out, uint32_t *miss_idx, int64_t *miss_keys,
                                    uint32_t *n_miss, void *stream) {
@@ -921,14 +1083,16 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     a.n_miss = n_miss;
     a.slot = next_slot(caches[0]);
     a.B = (uint32_t)batch;
-    const uint32_t tile = query_tile(caches[0]->W);
+    const QueryShape shape = query_shape(total);
+    const uint32_t tile = (uint32_t)(shape.kpw * shape.wpb);
     a.tiles_per_table = (uint32_t)((batch + tile - 1) / tile);
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
     a.g = make_geom(caches[0]->d);
     bool coherent = false;                      // any table that may see concurrent writers makes the call careful
     for (uint32_t t = 0; t < n_tables; ++t) coherent = coherent || caches[t]->concurrent_writers.load() != 0;
-    return launch_query(caches[0]->W, a, coherent, static_cast<hipStream_t>(stream));
+    const bool dedup = caches[0]->query_dedup.load() != 0;
+    return launch_query(caches[0]->W, a, shape, coherent, dedup, static_cast<hipStream_t>(stream));
 }
 
 hps_status_t hps_cache_query(hps_cache_t *c, const int64_t *keys, size_t n, float *out,

@@ -24,6 +24,7 @@ def dev(a, dtype=None):
 
 
 CONCURRENT_WRITERS = True      # which query variant new DeviceCache objects use (tests flip it)
+QUERY_DEDUP = False
 
 
 class DeviceCache:
@@ -35,6 +36,7 @@ class DeviceCache:
         assert self.S * self.W == capacity and self.W == ways and self.d == dim
         cw = CONCURRENT_WRITERS if concurrent_writers is None else concurrent_writers
         B.hps_cache_set_concurrent_writers(self.h, cw)
+        B.hps_cache_set_query_dedup(self.h, QUERY_DEDUP)
 
     def close(self):
         if self.h:

@@ -49,6 +49,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.hps_cache_destroy(None) == -1
     assert lib.hps_cache_info(None, None, None, None) == -1
     assert lib.hps_cache_set_concurrent_writers(None, 1) == -1
+    assert lib.hps_cache_set_query_dedup(None, 1) == -1
     assert lib.hps_cache_query_multi(None, 0, None, 0, None, None, None, None, None) == -1
     assert lib.hps_backing_fetch(None, 5, None, 6, 0, None, None, None, None) == -1
     assert lib.hps_backing_fetch(None, 5, None, 8, 0, None, None, None, None) == -1   # keys NULL

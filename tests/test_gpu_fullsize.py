@@ -66,7 +66,7 @@ def check_rows(out, keys, tags_hit_mask, versions, sample=None):
     assert (got[~hit] == SENTINEL).all(), "a miss row was written"
 
 
-@pytest.mark.parametrize("mode", ["plain", "checked"])
+@pytest.mark.parametrize("mode", ["plain", "checked", "dedup"])
 def test_c2_hot_cache_query_full_size(mode):
     S, W, d = 1 << 21, 8, 128
     n = 4096 * 26
@@ -75,6 +75,7 @@ def test_c2_hot_cache_query_full_size(mode):
     occupied = int((np.array(oc.keys) != EMPTY_KEY).sum())
     assert 0.84 < occupied / (S * W) < 0.88            # Poisson(8) loads truncated at 8 ways: about 0.86
     with DeviceCache(S * W, W, d, concurrent_writers=(mode == "checked")) as gc:
+        B.hps_cache_set_query_dedup(gc.h, mode == "dedup")
         gc.load(np.array(oc.keys), np.array(oc.ctr))
         assert refresh_cycle(gc, 0, 1 << 22) == occupied
         for seed in (1, 2, 500, 1000):

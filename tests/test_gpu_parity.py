@@ -21,14 +21,17 @@ from harness import (DeviceCache, EMPTY_KEY, RESERVED_KEY, SENTINEL, assert_same
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["checked", "plain"])
+@pytest.fixture(autouse=True, params=["checked", "plain", "dedup"])
 def query_variant(request):
-    """Every test runs against both query kernels: the one that validates rows against
-    concurrent writers (the default) and the plain one for query-only phases."""
+    """Every test runs against the three query kernels: the one that validates rows against
+    concurrent writers (the default), the plain one for query-only phases, and the plain one
+    with in-tile key deduplication."""
     import harness
     harness.CONCURRENT_WRITERS = request.param == "checked"
+    harness.QUERY_DEDUP = request.param == "dedup"
     yield request.param
     harness.CONCURRENT_WRITERS = True
+    harness.QUERY_DEDUP = False
 
 
 def rows_u32(keys, d, version=0):
