@@ -28,6 +28,10 @@ METRIC = "cache query Mkeys/s + achieved HBM GB/s (dim 128 fp32, Zipf keys)"
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--workload", choices=["query", "refresh"], default="query",
+                   help="query: the headline hot-cache query (default); refresh: dump every cached key, then "
+                        "update every cached row (the cache refresh of the paper's Table 3)")
+    p.add_argument("--capacity-gb", type=float, default=10.0, help="refresh: bytes of rows in the cache")
     p.add_argument("--steps", type=int, default=1000)
     p.add_argument("--warmup", type=int, default=50)
     p.add_argument("--log2-sets", type=int, default=21)
@@ -53,6 +57,84 @@ def parse():
     return p.parse_args()
 
 
+# Paper, Table 3 (A100-80GB, fp32 rows of 128): cache capacity GB -> (update ms, dump ms)
+PAPER_REFRESH = {1: (5.152, 0.064), 5: (25.177, 0.184), 10: (50.262, 0.335), 20: (100.530, 0.641),
+                 40: (200.345, 1.19)}
+
+
+def refresh(a, np, torch, B):
+    """Cache refresh (Sec. 6, steps 2-5; Table 3): Dump all cached keys, then Update every cached
+    row from a device-resident key-vector buffer.  A step is one full refresh."""
+    W, d = a.ways, a.dim
+    slots = int(a.capacity_gb * 1e9 / (4 * d)) // (W * 1024) * (W * 1024)
+    S = slots // W
+    h = B.hps_cache_create(slots, W, d)
+    B.hps_cache_set_concurrent_writers(h, True)
+    chunk = 1 << 20
+    ids = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    rows = torch.empty(chunk, d, dtype=torch.float32, device="cuda")
+    for lo in range(0, 2 * slots, chunk):                 # 2x the slots, so that practically every slot fills
+        m = min(chunk, 2 * slots - lo)
+        ids[:m] = torch.arange(lo, lo + m, dtype=torch.int64, device="cuda")
+        B.hps_backing_fetch(ids, m, d, version=0, rows=rows)
+        B.hps_cache_insert(h, ids, rows, m)
+    torch.cuda.synchronize()
+    del ids, rows
+    keys = torch.empty(slots, dtype=torch.int64, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    newrows = torch.empty(slots, d, dtype=torch.float32, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_dump, t_upd = [], []
+    for it in range(a.warmup + a.steps):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        B.hps_cache_dump(h, 0, slots, keys, cnt)
+        e1.record()
+        m = int(cnt.item())                                # the host needs the count to size the lookup (Sec. 6 step 3)
+        B.hps_backing_fetch(keys, m, d, version=it + 1, rows=newrows)
+        torch.cuda.synchronize()
+        e1b = ev()
+        e1b.record()
+        B.hps_cache_update(h, keys, newrows, m)
+        e2.record()
+        torch.cuda.synchronize()
+        if it >= a.warmup:
+            t_dump.append(e0.elapsed_time(e1))
+            t_upd.append(e1b.elapsed_time(e2))
+    # spot check: the cache now returns the rows of the last version
+    from paper_2210_08804_amd import inputs
+    probe = keys[:: max(1, m // 4096)][:4096].clone()
+    out = torch.zeros(len(probe), d, dtype=torch.float32, device="cuda")
+    mi = torch.empty(len(probe), dtype=torch.int32, device="cuda")
+    mk = torch.empty(len(probe), dtype=torch.int64, device="cuda")
+    nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.hps_cache_query(h, probe, len(probe), out, mi, mk, nm)
+    torch.cuda.synchronize()
+    exp = inputs.backing_rows(probe.cpu().numpy(), d, a.warmup + a.steps)
+    assert int(nm.item()) == 0 and (out.cpu().numpy().view(np.uint32) == exp.view(np.uint32)).all()
+    upd_ms, dump_ms = float(np.median(t_upd)), float(np.median(t_dump))
+    cap_gb = m * 4 * d / 1e9
+    paper = PAPER_REFRESH.get(int(round(a.capacity_gb))) if abs(a.capacity_gb - round(a.capacity_gb)) < 1e-6 else None
+    alg = m * (8 + 64 + 4 * d + 4 * d + 8)                 # key, key line, row in, row out, sequence word
+    res = {
+        "metric": "cache refresh GB/s (cached bytes / Update time, dim 128 fp32)", "value": round(cap_gb / (upd_ms * 1e-3), 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(upd_ms + dump_ms, 4),
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": round((cap_gb / (upd_ms * 1e-3)) / (a.capacity_gb / (paper[0] * 1e-3)), 2) if paper else None,
+        "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"cache refresh: dump + update of all {m} cached rows ({cap_gb:.2f} GB of rows, {S} sets x {W} ways, dim {d})",
+                   "update_ms": round(upd_ms, 4), "dump_ms": round(dump_ms, 4), "occupancy": round(m / slots, 4),
+                   "paper_table3_A100": {"update_ms": paper[0], "dump_ms": paper[1]} if paper else None},
+        "roofline": {"bound": "hbm", "achieved": round(alg / (upd_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(alg / (upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "write_kernel<8,false>", "algorithmic_bytes_per_launch": alg,
+                     "us_per_launch": round(upd_ms * 1e3, 1)},
+    }
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -68,6 +150,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     lib = B.load_library()
+    if a.workload == "refresh":
+        return refresh(a, np, torch, B)
 
     S, W, d = 1 << a.log2_sets, a.ways, a.dim
     slots = S * W

@@ -714,6 +714,97 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
     }
 }
 
+// Update (Alg. 4) with one lock acquisition per run of lanes that share a set.  Key batches that
+// come from a dump are in slot order: eight neighbouring keys belong to one set, and taking the
+// set's word once per key would serialise them over eight rounds.  Here adjacent pending lanes
+// with the same set form a group; the group's first lane reads the word and, if any lane of the
+// group found its key, takes it once; all those lanes' rows are then written under that one hold.
+// Two lanes of a group that found the same slot (a key given twice) are thinned to one per round.
+// Lanes of different groups that meet on a set compete by compare-and-swap as in write_kernel.
+template <int W>
+__global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
+    __shared__ uint64_t s_dst[kWavesPerWg][kWave];
+    __shared__ uint32_t s_srcrow[kWavesPerWg][kWave];
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    const RowGeom g = a.g;
+    const Table tb = a.tab;
+    uint32_t n = a.n;
+    if (a.n_dev) {
+        const uint32_t nd = *a.n_dev;
+        n = nd < n ? nd : n;
+    }
+    const uint32_t n_tiles = (n + kWave - 1) / kWave;
+    const uint32_t wave_global = blockIdx.x * kWavesPerWg + wave;
+    const uint32_t n_waves = gridDim.x * kWavesPerWg;
+    const uint64_t le_lane = lane == 63 ? ~0ull : ((2ull << lane) - 1);     // bits 0..lane
+
+    for (uint32_t tile = wave_global; tile < n_tiles; tile += n_waves) {
+        const uint32_t i = tile * kWave + lane;
+        const int64_t key = i < n ? a.keys[i] : kEmpty;
+        bool pending = i < n && !is_reserved(key);
+        const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
+
+        while (const uint64_t pendmask = __ballot(pending)) {
+            // groups: maximal runs of adjacent pending lanes with equal set
+            const uint32_t prev_set = (uint32_t)__shfl_up((int)set, 1, kWave);
+            const int prev_pend = __shfl_up((int)pending, 1, kWave);
+            const bool start = pending && (lane == 0 || !prev_pend || prev_set != set);
+            const uint64_t startmask = __ballot(start);
+            const int leader = pending ? 63 - __builtin_clzll(startmask & le_lane) : lane;
+            const uint64_t le_leader = leader == 63 ? ~0ull : ((2ull << leader) - 1);
+            const uint64_t above = startmask & ~le_leader;
+            const uint64_t lt_end = above ? ((1ull << __builtin_ctzll(above)) - 1) : ~0ull;
+            const uint64_t gmask = pendmask & lt_end & ~(le_leader >> 1);    // lanes leader .. end-1 that are pending
+            const bool is_leader = pending && lane == leader;
+
+            uint32_t v = is_leader ? ld_agent(tb.seq + set) : 0u;
+            v = (uint32_t)__shfl((int)v, leader, kWave);
+            const bool busy = pending && (v & 1u);
+            shared_acquire();                                        // the word is read before the keys
+            int way = -1;
+            if (pending && !busy) {
+#pragma unroll
+                for (int w = 0; w < W; ++w)
+                    if (ld_agent(tb.K + (uint64_t)set * W + w) == key) way = w;
+                if (way < 0) pending = false;                        // not cached: ignored
+            }
+            bool winner = pending && !busy && way >= 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {                            // one lane per slot and round
+                const uint64_t m = __ballot(winner && way == w) & gmask;
+                if (winner && way == w && lane != __builtin_ctzll(m)) winner = false;
+            }
+            const bool group_needs = (__ballot(winner) & gmask) != 0;
+            bool won = false;
+            if (is_leader && !busy && group_needs) {
+                uint32_t expect = v;
+                won = __hip_atomic_compare_exchange_strong(tb.seq + set, &expect, v + 1u, __ATOMIC_RELAXED,
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const bool gwon = __shfl((int)won, leader, kWave) != 0;
+            const bool act = winner && gwon;
+            const uint64_t actmask = __ballot(act);
+            if (actmask) {
+                shared_acquire();
+                if (act) {
+                    const int r = rank_in(actmask);
+                    s_dst[wave][r] = (uint64_t)set * W + (uint32_t)way;
+                    s_srcrow[wave][r] = i;
+                }
+                wave_lds_fence();
+                copy_rows_shared<8>(g, a.vals, tb.V, &s_srcrow[wave][0], &s_dst[wave][0],
+                                    (uint32_t)__popcll(actmask));
+                wave_lds_fence();
+                shared_release();                                    // rows land before the word moves on
+                if (won) st_agent(tb.seq + set, v + 2u);
+                if (act) pending = false;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ small kernels
 
 __global__ void fill_keys_kernel(int64_t *K, uint64_t n, int64_t v) {
@@ -728,40 +819,65 @@ __global__ void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v) {
         p[i] = v;
 }
 
-// Dump (Sec. 4.2): compact the non-empty keys of a slot range.  Same counter-word scheme as query.
+// Dump (Sec. 4.2): compact the non-empty keys of a slot range.  A work-group takes a tile of
+// 256*KPT slots, keeps KPT keys per lane in registers, and needs one counter atomic per tile
+// (same counter-word scheme as query).  Inside a tile the slots are visited set-major
+// (q -> set q mod SPT, way q div SPT, SPT = sets per tile), so keys of one set end up SPT
+// entries apart in the output instead of next to each other.
+template <int KPT>
 __global__ void __launch_bounds__(kBlock) dump_kernel(const int64_t *__restrict__ K, uint64_t first,
-                                                      uint64_t n_slots, int64_t *keys_out,
+                                                      uint64_t n_slots, uint32_t W, int64_t *keys_out,
                                                       uint32_t *n_out, uint64_t *slot,
                                                       uint32_t n_tiles) {
-    __shared__ uint32_t s_wcnt[kWavesPerWg];
+    constexpr uint32_t kTileSlots = kBlock * KPT;
+    static_assert(KPT * kWavesPerWg <= kWave, "the count scan runs in one wave");
+    __shared__ uint32_t s_cnt[KPT * kWavesPerWg];          // [j][wave] counts, then exclusive prefixes
     __shared__ uint32_t s_base;
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
+    const uint32_t spt = kTileSlots / W;                  // W <= 64 divides 256*KPT
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t i = (uint64_t)tile * kBlock + threadIdx.x;
-        const int64_t key = i < n_slots ? K[first + i] : kEmpty;
-        const bool full = key != kEmpty;
-        const uint64_t m = __ballot(full);
-        if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(m);
-        __syncthreads();
-        uint32_t woff = 0, total = 0;
+        int64_t key[KPT];
+        uint32_t rank[KPT];
 #pragma unroll
-        for (int w = 0; w < kWavesPerWg; ++w) {
-            const uint32_t c = s_wcnt[w];
-            woff += (w < wave) ? c : 0u;
-            total += c;
+        for (int j = 0; j < KPT; ++j) {
+            const uint32_t q = (uint32_t)j * kBlock + threadIdx.x;
+            const uint64_t i = (uint64_t)tile * kTileSlots + (uint64_t)(q % spt) * W + q / spt;
+            key[j] = i < n_slots ? K[first + i] : kEmpty;
         }
-        if (threadIdx.x == 0) {
-            const uint64_t old = __hip_atomic_fetch_add(slot, (1ull << 32) | (uint64_t)total,
-                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_base = (uint32_t)old;
-            if ((uint32_t)(old >> 32) + 1u == n_tiles) {
-                *n_out = (uint32_t)old + total;
-                __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const uint64_t m = __ballot(key[j] != kEmpty);
+            rank[j] = (uint32_t)rank_in(m);
+            if (lane == 0) s_cnt[j * kWavesPerWg + wave] = (uint32_t)__popcll(m);
+        }
+        __syncthreads();
+        if (wave == 0) {                                   // exclusive scan of the KPT*4 (<= 64) counts
+            const uint32_t c = lane < KPT * kWavesPerWg ? s_cnt[lane] : 0u;
+            uint32_t incl = c;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const uint32_t up = (uint32_t)__shfl_up((int)incl, o, kWave);
+                if (lane >= o) incl += up;
+            }
+            if (lane < KPT * kWavesPerWg) s_cnt[lane] = incl - c;
+            const uint32_t total = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+            if (lane == 0) {
+                const uint64_t old = __hip_atomic_fetch_add(slot, (1ull << 32) | (uint64_t)total,
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_base = (uint32_t)old;
+                if ((uint32_t)(old >> 32) + 1u == n_tiles) {
+                    *n_out = (uint32_t)old + total;
+                    __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
         __syncthreads();
-        if (full) keys_out[s_base + woff + (uint32_t)rank_in(m)] = key;
+        const uint32_t base = s_base;
+#pragma unroll
+        for (int j = 0; j < KPT; ++j)
+            if (key[j] != kEmpty) keys_out[base + s_cnt[j * kWavesPerWg + wave] + rank[j]] = key[j];
+        __syncthreads();
     }
 }
 
@@ -937,7 +1053,11 @@ hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, 
     if (blocks > (1u << 16)) blocks = 1u << 16;
     const dim3 grid((uint32_t)blocks), block(kBlock);
     switch (c->W) {
-#define HPS_CASE(w) case w: hipLaunchKernelGGL((write_kernel<w, kInsert>), grid, block, 0, st, a); break;
+#define HPS_CASE(w)                                                                         \
+    case w:                                                                                 \
+        if (kInsert) hipLaunchKernelGGL((write_kernel<w, true>), grid, block, 0, st, a);    \
+        else hipLaunchKernelGGL((update_kernel<w>), grid, block, 0, st, a);                 \
+        break;
         HPS_CASE(1) HPS_CASE(2) HPS_CASE(4) HPS_CASE(8) HPS_CASE(16) HPS_CASE(32) HPS_CASE(64)
 #undef HPS_CASE
         default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
@@ -1155,11 +1275,12 @@ hps_status_t hps_cache_dump(hps_cache_t *c, size_t first_slot, size_t n_slots, i
     if (n_slots >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n_slots must be < 2^32 per call");
     if (!n_out || (n_slots > 0 && !keys_out)) return fail(HPS_ERR_INVALID_ARG, "output pointer is NULL");
     if (!aligned(keys_out, 8) || !aligned(n_out, 4)) return fail(HPS_ERR_INVALID_ARG, "misaligned output buffer");
-    uint32_t n_tiles = (uint32_t)((n_slots + kBlock - 1) / kBlock);
+    constexpr int kDumpKpt = 16;                       // 4096 slots per tile
+    uint32_t n_tiles = (uint32_t)((n_slots + kBlock * kDumpKpt - 1) / (kBlock * kDumpKpt));
     if (n_tiles == 0) n_tiles = 1;
-    const uint32_t grid = n_tiles < (1u << 16) ? n_tiles : (1u << 16);
-    hipLaunchKernelGGL(dump_kernel, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), c->K,
-                       (uint64_t)first_slot, (uint64_t)n_slots, keys_out, n_out, next_slot(c), n_tiles);
+    const uint32_t grid = n_tiles < (1u << 20) ? n_tiles : (1u << 20);
+    hipLaunchKernelGGL((dump_kernel<kDumpKpt>), dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), c->K,
+                       (uint64_t)first_slot, (uint64_t)n_slots, c->W, keys_out, n_out, next_slot(c), n_tiles);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
