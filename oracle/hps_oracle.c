@@ -22,11 +22,15 @@
  *   - Geometry: a set has W slots (W a power of two, 1..64); the paper's 32-slot slabs and
  *     the choice of the first slab to probe only permute the search order inside one set
  *     and cannot change any result, so they do not appear here.
- *   - Victim choice: the paper picks the least-recently-used slot from per-slot access
- *     counters.  This build's contract replaces that by one counter per set:
+ *   - Victim choice, policy 0 (this build's contract): one counter per set,
  *     way = C[s] mod W, then C[s] += 1.  Because nothing is ever deleted, that fills
  *     ways 0..W-1 first ("empty slots first") and afterwards evicts in insertion order.
- *     Query is therefore read-only.
+ *     Query is then read-only.
+ *   - Victim choice, policy 1 (the paper's, Sec. 4.2 Replace, Alg. 2-3): every slot has an
+ *     access stamp T; a global iteration count g goes up by one per Query call; a Query hit and
+ *     a Replace of an already cached key set T = g; a new key takes the lowest-numbered empty
+ *     slot, else the least recently used slot (largest g - T mod 2^32, lowest way on ties),
+ *     and gets T = g.  Update leaves stamps alone (Alg. 4).
  *   - Hash: the paper names none.  set = (upper 32 bits of mix64(key)) mod S where mix64 is
  *     the 64-bit finaliser of the splitmix64 generator.
  *   - Empty marker: INT64_MIN ("Null" in Alg. 2-4).  INT64_MIN and INT64_MIN+1 are reserved:
@@ -50,7 +54,10 @@ typedef struct {
     uint32_t d;      /* 32-bit words per row                  */
     int64_t  *K;     /* [S][W]    keys, HPSO_EMPTY when free  */
     uint32_t *V;     /* [S][W][d] rows as bit patterns        */
-    uint32_t *C;     /* [S]       per-set victim counter      */
+    uint32_t *C;     /* [S]       per-set victim counter (policy 0); number of inserts (policy 1) */
+    uint32_t policy; /* 0 = victim counter, 1 = LRU by access stamp */
+    uint32_t *T;     /* [S][W]    access stamps (policy 1)    */
+    uint32_t g;      /* global iteration count (policy 1)     */
 } hpso_t;
 
 /* Finaliser of splitmix64: three xor-shifts around two odd multipliers, all mod 2^64. */
@@ -85,10 +92,10 @@ static int find_way(const hpso_t *c, uint64_t s, int64_t key)
     return -1;
 }
 
-hpso_t *hpso_create(uint64_t capacity, uint32_t W, uint32_t d)
+hpso_t *hpso_create_policy(uint64_t capacity, uint32_t W, uint32_t d, uint32_t policy)
 {
     if (W == 0 || W > 64 || (W & (W - 1)) != 0 || d == 0 || capacity == 0 ||
-        capacity % W != 0 || capacity / W >= (1ULL << 31))
+        capacity % W != 0 || capacity / W >= (1ULL << 31) || policy > 1)
         return NULL;
     hpso_t *c = (hpso_t *)calloc(1, sizeof(hpso_t));
     if (!c) return NULL;
@@ -98,18 +105,26 @@ hpso_t *hpso_create(uint64_t capacity, uint32_t W, uint32_t d)
     c->K = (int64_t *)malloc(sizeof(int64_t) * capacity);
     c->V = (uint32_t *)calloc(capacity * (uint64_t)d, sizeof(uint32_t));
     c->C = (uint32_t *)calloc(c->S, sizeof(uint32_t));
-    if (!c->K || !c->V || !c->C) {
-        free(c->K); free(c->V); free(c->C); free(c);
+    c->T = (uint32_t *)calloc(capacity, sizeof(uint32_t));
+    c->policy = policy;
+    c->g = 0;
+    if (!c->K || !c->V || !c->C || !c->T) {
+        free(c->K); free(c->V); free(c->C); free(c->T); free(c);
         return NULL;
     }
     for (uint64_t i = 0; i < capacity; ++i) c->K[i] = HPSO_EMPTY;
     return c;
 }
 
+hpso_t *hpso_create(uint64_t capacity, uint32_t W, uint32_t d)
+{
+    return hpso_create_policy(capacity, W, d, 0);
+}
+
 void hpso_destroy(hpso_t *c)
 {
     if (!c) return;
-    free(c->K); free(c->V); free(c->C); free(c);
+    free(c->K); free(c->V); free(c->C); free(c->T); free(c);
 }
 
 uint64_t  hpso_num_sets(const hpso_t *c) { return c->S; }
@@ -118,15 +133,19 @@ uint32_t  hpso_dim(const hpso_t *c)      { return c->d; }
 int64_t  *hpso_keys(hpso_t *c)           { return c->K; }
 uint32_t *hpso_vals(hpso_t *c)           { return c->V; }
 uint32_t *hpso_ctr(hpso_t *c)            { return c->C; }
+uint32_t *hpso_stamps(hpso_t *c)         { return c->T; }
+uint32_t  hpso_get_g(const hpso_t *c)    { return c->g; }
+void      hpso_set_g(hpso_t *c, uint32_t g) { c->g = g; }
 
 /*
  * Query (Alg. 2).  out is [n][d]; rows of missing positions are left untouched.
  * miss_idx / miss_keys receive <index, key> in ascending index order.  Returns |M|.
  */
-uint64_t hpso_query(const hpso_t *c, const int64_t *keys, uint64_t n,
+uint64_t hpso_query(hpso_t *c, const int64_t *keys, uint64_t n,
                     uint32_t *out, uint32_t *miss_idx, int64_t *miss_keys)
 {
     uint64_t n_miss = 0;
+    if (c->policy == 1) c->g += 1;                     /* Alg. 2: g <- g + 1, Query only */
     for (uint64_t i = 0; i < n; ++i) {
         int64_t q = keys[i];
         int w = -1;
@@ -142,21 +161,40 @@ uint64_t hpso_query(const hpso_t *c, const int64_t *keys, uint64_t n,
         } else {
             memcpy(out + i * c->d, c->V + (s * c->W + (uint64_t)w) * c->d,
                    sizeof(uint32_t) * c->d);
+            if (c->policy == 1) c->T[s * c->W + (uint64_t)w] = c->g;   /* refresh the counter */
         }
     }
     return n_miss;
 }
 
-/* Replace (Alg. 3) with the per-set victim counter as the slot choice. */
+/* Replace (Alg. 3); the slot of a new key is chosen by the cache's policy (see the header). */
 void hpso_insert(hpso_t *c, const int64_t *keys, const uint32_t *vals, uint64_t n)
 {
     for (uint64_t i = 0; i < n; ++i) {
         int64_t q = keys[i];
         if (is_reserved(q)) continue;
         uint64_t s = hpso_set_of(c, q);
-        if (find_way(c, s, q) >= 0) continue;          /* already cached: ignored */
-        uint32_t w = c->C[s] % c->W;
-        c->C[s] += 1;                                   /* wraps mod 2^32; W divides 2^32 */
+        int f = find_way(c, s, q);
+        if (f >= 0) {                                   /* already cached: row ignored */
+            if (c->policy == 1) c->T[s * c->W + (uint64_t)f] = c->g;
+            continue;
+        }
+        uint32_t w;
+        if (c->policy == 0) {
+            w = c->C[s] % c->W;                         /* wraps mod 2^32; W divides 2^32 */
+        } else {
+            int e = find_way(c, s, HPSO_EMPTY);         /* empty slots first */
+            if (e >= 0) {
+                w = (uint32_t)e;
+            } else {                                    /* least recently used: largest age */
+                w = 0;
+                for (uint32_t x = 1; x < c->W; ++x)
+                    if ((uint32_t)(c->g - c->T[s * c->W + x]) > (uint32_t)(c->g - c->T[s * c->W + w]))
+                        w = x;
+            }
+            c->T[s * c->W + w] = c->g;
+        }
+        c->C[s] += 1;
         c->K[s * c->W + w] = q;
         memcpy(c->V + (s * c->W + w) * c->d, vals + i * c->d, sizeof(uint32_t) * c->d);
     }

@@ -28,13 +28,19 @@ def _load():
     lib.hpso_mix64.argtypes = [u64]
     lib.hpso_create.restype = vp
     lib.hpso_create.argtypes = [u64, u32, u32]
+    lib.hpso_create_policy.restype = vp
+    lib.hpso_create_policy.argtypes = [u64, u32, u32, u32]
+    lib.hpso_get_g.restype = u32
+    lib.hpso_get_g.argtypes = [vp]
+    lib.hpso_set_g.restype = None
+    lib.hpso_set_g.argtypes = [vp, u32]
     lib.hpso_destroy.restype = None
     lib.hpso_destroy.argtypes = [vp]
     lib.hpso_set_of.restype = u64
     lib.hpso_set_of.argtypes = [vp, C.c_int64]
     lib.hpso_num_sets.restype = u64
     lib.hpso_num_sets.argtypes = [vp]
-    for name in ("hpso_keys", "hpso_vals", "hpso_ctr"):
+    for name in ("hpso_keys", "hpso_vals", "hpso_ctr", "hpso_stamps"):
         getattr(lib, name).restype = vp
         getattr(lib, name).argtypes = [vp]
     lib.hpso_query.restype = u64
@@ -72,10 +78,12 @@ def _rows(a, n, d):
 class OracleCache:
     """One set-associative cache of `capacity` slots, `ways` slots per set, `dim` words per row."""
 
-    def __init__(self, capacity: int, ways: int, dim: int):
+    def __init__(self, capacity: int, ways: int, dim: int, policy: int = 0):
+        """policy 0: per-set victim counter; policy 1: LRU by access stamp (the paper's rule)."""
         lib = _load()
         self._lib = lib
-        self._h = lib.hpso_create(capacity, ways, dim)
+        self.policy = policy
+        self._h = lib.hpso_create_policy(capacity, ways, dim, policy)
         if not self._h:
             raise ValueError("invalid cache geometry")
         self.S = int(lib.hpso_num_sets(self._h))
@@ -88,11 +96,13 @@ class OracleCache:
             C.cast(lib.hpso_vals(self._h), C.POINTER(C.c_uint32)), shape=(self.S, self.W, dim))
         self.ctr = np.ctypeslib.as_array(
             C.cast(lib.hpso_ctr(self._h), C.POINTER(C.c_uint32)), shape=(self.S,))
+        self.stamps = np.ctypeslib.as_array(
+            C.cast(lib.hpso_stamps(self._h), C.POINTER(C.c_uint32)), shape=(self.S, self.W))
         assert self.keys.size == n
 
     def close(self):
         if self._h:
-            self.keys = self.vals = self.ctr = None
+            self.keys = self.vals = self.ctr = self.stamps = None
             self._lib.hpso_destroy(self._h)
             self._h = None
 
@@ -101,6 +111,14 @@ class OracleCache:
             self.close()
         except Exception:
             pass
+
+    @property
+    def g(self) -> int:
+        return int(self._lib.hpso_get_g(self._h))
+
+    @g.setter
+    def g(self, value: int):
+        self._lib.hpso_set_g(self._h, value & 0xFFFFFFFF)
 
     def set_of(self, key: int) -> int:
         return int(self._lib.hpso_set_of(self._h, C.c_int64(key)))
@@ -134,8 +152,10 @@ class OracleCache:
         m = self._lib.hpso_dump(self._h, buf.ctypes.data)
         return buf[:m].copy()
 
-    def load_state(self, keys, ctr, vals=None):
+    def load_state(self, keys, ctr, vals=None, stamps=None):
         """Overwrite the whole state (used to re-seat the oracle after an overflowing batch)."""
+        if stamps is not None:
+            self.stamps[...] = np.asarray(stamps, dtype=np.uint32).reshape(self.S, self.W)
         self.keys[...] = np.asarray(keys, dtype=np.int64).reshape(self.S, self.W)
         self.ctr[...] = np.asarray(ctr, dtype=np.uint32).reshape(self.S)
         if vals is not None:
