@@ -32,6 +32,8 @@ def parse():
                    help="query: the headline hot-cache query (default); refresh: dump every cached key, then "
                         "update every cached row (the cache refresh of the paper's Table 3)")
     p.add_argument("--capacity-gb", type=float, default=10.0, help="refresh: bytes of rows in the cache")
+    p.add_argument("--policy", choices=["counter", "lru"], default="counter",
+                   help="replacement policy of the cache: per-set victim counter (default) or the paper's LRU stamps")
     p.add_argument("--steps", type=int, default=1000)
     p.add_argument("--warmup", type=int, default=50)
     p.add_argument("--log2-sets", type=int, default=21)
@@ -160,7 +162,8 @@ def main():
     t_setup = time.time()
 
     # ---- cache + prefill: ids slots-1 .. 0 in descending chunks, rows from the device-side backing stand-in
-    h = B.hps_cache_create(slots, W, d)
+    h = (B.hps_cache_create(slots, W, d) if a.policy == "counter"
+         else B.hps_cache_create_policy(slots, W, d, B.HPS_POLICY_LRU))
     chunk = 1 << 18
     ids = torch.empty(chunk, dtype=torch.int64, device="cuda")
     rows = torch.empty(chunk, d, dtype=torch.float32, device="cuda")
@@ -304,6 +307,7 @@ def main():
                          f" = {n} int64 keys, {a.keys} alpha={a.alpha} over {a.key_space} ids, seeds 1.."),
             "hit_rate": round(hit_rate, 4), "distinct_key_fraction": round(float(np.mean(distinct_frac)), 4),
             "out_buffers_rotated": a.out_buffers, "concurrent_writer_checks": bool(a.coherent),
+            "replacement_policy": a.policy,
             "launch": "hip graph" if graph is not None else "eager, one call per batch",
             "repeat_ms": [round(t, 3) for t in times],
         },

@@ -44,6 +44,10 @@ typedef enum {
 
 #define HPS_MAX_TABLES 32               /* most tables one hps_cache_query_multi call takes */
 
+/* Replacement policies (which slot a new key takes when its set is full). */
+#define HPS_POLICY_VICTIM_COUNTER 0     /* per-set counter, insertion order (hps_cache_create) */
+#define HPS_POLICY_LRU            1     /* least recently used by access stamp (Sec. 4.2, Alg. 2-3) */
+
 /*
  * Create a cache of `capacity` slots organised as capacity/ways sets of `ways` slots
  * (Sec. 4.1: a key hashes to one set and may occupy any slot of it), rows of `dim` fp32.
@@ -57,6 +61,17 @@ typedef enum {
  */
 hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim,
                               hps_cache_t **out_handle);
+
+/*
+ * As hps_cache_create, with the replacement policy chosen.  HPS_POLICY_LRU is the paper's rule
+ * (Sec. 4.2 "Replace", Alg. 2-3): every slot carries an access stamp; each query call advances a
+ * global iteration count g and stamps the slots it hits with it; insert stamps an already cached
+ * key, puts a new key into the lowest-numbered empty slot of its set or else over the least
+ * recently used one (largest g - stamp modulo 2^32, lowest way on ties) and stamps it.  Update
+ * leaves stamps alone (Alg. 4).  Costs 4 bytes per slot and one scattered 4-byte store per hit.
+ */
+hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t dim, int policy,
+                                     hps_cache_t **out_handle);
 
 /* Free everything the cache owns.  The caller must have synchronised all streams that used it. */
 hps_status_t hps_cache_destroy(hps_cache_t *cache);
@@ -138,6 +153,13 @@ hps_status_t hps_cache_export(hps_cache_t *cache, int64_t *keys, uint32_t *ctr, 
                               void *stream);
 hps_status_t hps_cache_import(hps_cache_t *cache, const int64_t *keys, const uint32_t *ctr,
                               const float *vals, void *stream);
+
+/*
+ * LRU caches only: the access stamps (stamps [device, sets*ways uint32], [set][way] order) and
+ * the global iteration count (*g [host] on export).  Complements hps_cache_export/import.
+ */
+hps_status_t hps_cache_export_lru(hps_cache_t *cache, uint32_t *stamps, uint32_t *g, void *stream);
+hps_status_t hps_cache_import_lru(hps_cache_t *cache, const uint32_t *stamps, uint32_t g, void *stream);
 
 /*
  * Dump (Sec. 4.2 "Dump"; step 2 of the refresh cycle, Sec. 6): write the cached keys of the

@@ -18,12 +18,15 @@ HPS_ERR_INVALID_ARG = -1
 HPS_ERR_OOM = -2
 HPS_ERR_DEVICE = -3
 HPS_MAX_TABLES = 32
+HPS_POLICY_VICTIM_COUNTER = 0
+HPS_POLICY_LRU = 1
 
 EXPORTS = (
     "hps_cache_create", "hps_cache_destroy", "hps_cache_query", "hps_cache_insert",
     "hps_cache_update", "hps_last_error", "hps_cache_set_concurrent_writers", "hps_cache_info",
     "hps_cache_export", "hps_cache_import", "hps_cache_dump", "hps_cache_query_multi",
     "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn", "hps_cache_set_query_dedup",
+    "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
 )
 
 _lib = None
@@ -50,6 +53,9 @@ def load_library():
     lib.hps_last_error.argtypes = []
     sigs = {
         "hps_cache_create": [sz, u32, u32, C.POINTER(vp)],
+        "hps_cache_create_policy": [sz, u32, u32, C.c_int, C.POINTER(vp)],
+        "hps_cache_export_lru": [vp, vp, C.POINTER(u32), vp],
+        "hps_cache_import_lru": [vp, vp, u32, vp],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
         "hps_cache_insert": [vp, vp, vp, sz, vp],
@@ -99,6 +105,22 @@ def hps_cache_create(capacity: int, ways: int, dim: int) -> int:
     h = C.c_void_p()
     _check(load_library().hps_cache_create(capacity, ways, dim, C.byref(h)))
     return h.value
+
+
+def hps_cache_create_policy(capacity: int, ways: int, dim: int, policy: int) -> int:
+    h = C.c_void_p()
+    _check(load_library().hps_cache_create_policy(capacity, ways, dim, policy, C.byref(h)))
+    return h.value
+
+
+def hps_cache_export_lru(handle, stamps, stream=None) -> int:
+    g = C.c_uint32()
+    _check(load_library().hps_cache_export_lru(handle, _ptr(stamps, torch.int32), C.byref(g), _stream(stream)))
+    return g.value
+
+
+def hps_cache_import_lru(handle, stamps, g: int, stream=None) -> None:
+    _check(load_library().hps_cache_import_lru(handle, _ptr(stamps, torch.int32), g, _stream(stream)))
 
 
 def hps_cache_destroy(handle) -> None:

@@ -5,6 +5,7 @@
 //   V   fp32   [S][W][d]   rows, 16-byte aligned, moved as opaque 128-bit chunks
 //   ctr uint32 [S]         victim counter: next way of the set = ctr mod W
 //   seq uint32 [S]         sequence word: odd while a writer owns the set (lock + seqlock)
+//   T   uint32 [S][W]      access stamps, only for caches created with the LRU policy
 //
 // Paper passages: data model Sec. 4.1; Query Alg. 2; Replace Alg. 3; Update Alg. 4; Dump and
 // the asynchronous, batch-in calling convention Sec. 4.2.  The paper's per-slabset warp lock
@@ -143,6 +144,8 @@ struct Table {                 // one cache as the kernels see it
     uint32_t *seq;
     uint32_t  S;
     uint32_t  smask;           // S - 1 when S is a power of two, else 0
+    uint32_t *T;               // [S][W] access stamps, LRU policy only (else nullptr)
+    uint32_t  g;               // the call's global iteration count (LRU policy)
 };
 
 // Row geometry shared by all copy loops: a row is C = d/4 chunks of 16 bytes; LPR lanes
@@ -429,6 +432,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 s_mkey[wave][r] = key;
             }
             if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(missmask);
+            if (tb.T && hit) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);   // Alg. 2: refresh the counter
 
             if (kCoherent) {
                 __syncthreads();                           // rows were copied inside the retry loop
@@ -540,6 +544,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
             const uint32_t rep = is_rep ? tid : (want ? h_own[my] : tid);
             const int way = probe_wave<W, kWave>(tb.K, key, set, is_rep);
             if (is_rep) r_slot[tid] = way >= 0 ? (uint64_t)set * W + (uint32_t)way : kMissed;
+            if (tb.T && is_rep && way >= 0) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);
             __syncthreads();                                    // #3 probe results visible
             const uint64_t res = want ? r_slot[rep] : kMissed;
             const bool hit = res != kMissed;
@@ -669,15 +674,20 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
             bool won = false;
             uint32_t v = 0;
             int way = -1;
+            int empty_way = -1;
             if (pending) {
                 v = ld_agent(tb.seq + set);
                 if (!(v & 1u)) {
 #pragma unroll
-                    for (int w = 0; w < W; ++w)
-                        if (ld_agent(tb.K + (uint64_t)set * W + w) == key) way = w;
+                    for (int w = W - 1; w >= 0; --w) {
+                        const int64_t kw = ld_agent(tb.K + (uint64_t)set * W + w);
+                        if (kw == key) way = w;
+                        if (kw == kEmpty) empty_way = w;      // ends as the lowest empty way
+                    }
                     const bool found = way >= 0;
                     if (found == kInsert) {
                         pending = false;                      // insert: already cached; update: absent
+                        if (kInsert && tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);   // Alg. 3: refresh
                     } else {
                         uint32_t expect = v;
                         won = __hip_atomic_compare_exchange_strong(
@@ -692,7 +702,20 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
                 if (won) {
                     if (kInsert) {
                         const uint32_t c = ld_agent(tb.ctr + set);
-                        way = (int)(c & (W - 1));
+                        if (!tb.T) {
+                            way = (int)(c & (W - 1));                 // victim counter
+                        } else if (empty_way >= 0) {
+                            way = empty_way;                          // empty slots first
+                        } else {                                      // least recently used: largest age
+                            uint32_t best = 0;
+                            way = 0;
+#pragma unroll
+                            for (int w = 0; w < W; ++w) {
+                                const uint32_t age = tb.g - ld_agent(tb.T + (uint64_t)set * W + w);
+                                if (w == 0 || age > best) { best = age; way = w; }
+                            }
+                        }
+                        if (tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);
                         st_agent(tb.ctr + set, c + 1u);
                         st_agent(tb.K + (uint64_t)set * W + way, key);
                     }
@@ -948,6 +971,9 @@ struct hps_cache {
     std::atomic<uint32_t> calls;
     std::atomic<int> concurrent_writers;
     std::atomic<int> query_dedup;
+    int      policy;                      // HPS_POLICY_*
+    uint32_t *T;                          // access stamps (LRU policy), else nullptr
+    std::atomic<uint32_t> g;              // global iteration count: one step per query call (LRU policy)
 };
 
 namespace {
@@ -971,6 +997,8 @@ Table table_of(const hps_cache *c) {
     t.S = (uint32_t)c->S;
     t.smask = (c->S & (c->S - 1)) == 0 ? (uint32_t)(c->S - 1) : 0u;
     if (c->S == 1) t.smask = 0;           // S = 1: "h % 1" = 0 (a zero mask means "use modulo")
+    t.T = c->T;
+    t.g = c->g.load(std::memory_order_relaxed);
     return t;
 }
 
@@ -1088,8 +1116,15 @@ extern "C" {
 const char *hps_last_error(void) { return g_err.c_str(); }
 
 hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim, hps_cache_t **out_handle) {
+    return hps_cache_create_policy(capacity, ways, dim, HPS_POLICY_VICTIM_COUNTER, out_handle);
+}
+
+hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t dim, int policy,
+                                     hps_cache_t **out_handle) {
     if (!out_handle) return fail(HPS_ERR_INVALID_ARG, "out_handle is NULL");
     *out_handle = nullptr;
+    if (policy != HPS_POLICY_VICTIM_COUNTER && policy != HPS_POLICY_LRU)
+        return fail(HPS_ERR_INVALID_ARG, "unknown replacement policy");
     if (ways == 0 || ways > 64 || (ways & (ways - 1)) != 0)
         return fail(HPS_ERR_INVALID_ARG, "ways must be a power of two in [1, 64]");
     if (capacity == 0 || capacity % ways != 0)
@@ -1104,7 +1139,9 @@ hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim, hps_
     c->S = capacity / ways;
     c->W = ways;
     c->d = dim;
-    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr;
+    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr;
+    c->policy = policy;
+    c->g.store(0);
     c->calls.store(0);
     c->concurrent_writers.store(1);
     c->query_dedup.store(0);
@@ -1115,6 +1152,10 @@ hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim, hps_
     if (e == hipSuccess) e = hipMalloc(&c->ctr, c->S * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->seq, c->S * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->ring, kRing * sizeof(uint64_t));
+    if (e == hipSuccess && policy == HPS_POLICY_LRU) {
+        e = hipMalloc(&c->T, capacity * sizeof(uint32_t));
+        if (e == hipSuccess) e = hipMemsetAsync(c->T, 0, capacity * sizeof(uint32_t), 0);
+    }
     if (e == hipSuccess) {
         hipLaunchKernelGGL(fill_keys_kernel, dim3(4096), dim3(256), 0, 0, c->K, (uint64_t)capacity, kEmpty);
         e = hipGetLastError();
@@ -1133,6 +1174,7 @@ hps_status_t hps_cache_create(size_t capacity, uint32_t ways, uint32_t dim, hps_
         if (c->ctr) (void)hipFree(c->ctr);
         if (c->seq) (void)hipFree(c->seq);
         if (c->ring) (void)hipFree(c->ring);
+        if (c->T) (void)hipFree(c->T);
         delete c;
         return fail(code, msg);
     }
@@ -1149,6 +1191,7 @@ hps_status_t hps_cache_destroy(hps_cache_t *c) {
     if ((e2 = hipFree(c->ctr)) != hipSuccess) e = e2;
     if ((e2 = hipFree(c->seq)) != hipSuccess) e = e2;
     if ((e2 = hipFree(c->ring)) != hipSuccess) e = e2;
+    if (c->T && (e2 = hipFree(c->T)) != hipSuccess) e = e2;
     delete c;
     if (e != hipSuccess) return fail(HPS_ERR_DEVICE, std::string("hipFree: ") + hipGetErrorString(e));
     return HPS_OK;
@@ -1195,7 +1238,10 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     }
     QueryArgs a;
     std::memset(&a, 0, sizeof(a));
-    for (uint32_t t = 0; t < n_tables; ++t) a.tab[t] = table_of(caches[t]);
+    for (uint32_t t = 0; t < n_tables; ++t) {
+        if (caches[t]->policy == HPS_POLICY_LRU) caches[t]->g.fetch_add(1, std::memory_order_relaxed);   // Alg. 2: g <- g + 1
+        a.tab[t] = table_of(caches[t]);
+    }
     a.keys = keys;
     a.out = out;
     a.miss_idx = miss_idx;
@@ -1263,6 +1309,26 @@ hps_status_t hps_cache_import(hps_cache_t *c, const int64_t *keys, const uint32_
         HIP_TRY(hipMemcpyAsync(c->V, vals, slots * c->d * sizeof(float), hipMemcpyDeviceToDevice, st));
     hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, c->seq, (uint64_t)c->S, 0u);
     HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_export_lru(hps_cache_t *c, uint32_t *stamps, uint32_t *g, void *stream) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (c->policy != HPS_POLICY_LRU) return fail(HPS_ERR_INVALID_ARG, "the cache was not created with the LRU policy");
+    if (!stamps || !g) return fail(HPS_ERR_INVALID_ARG, "stamps and g must not be NULL");
+    HIP_TRY(hipMemcpyAsync(stamps, c->T, c->S * c->W * sizeof(uint32_t), hipMemcpyDeviceToDevice,
+                           static_cast<hipStream_t>(stream)));
+    *g = c->g.load();
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_import_lru(hps_cache_t *c, const uint32_t *stamps, uint32_t g, void *stream) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (c->policy != HPS_POLICY_LRU) return fail(HPS_ERR_INVALID_ARG, "the cache was not created with the LRU policy");
+    if (!stamps) return fail(HPS_ERR_INVALID_ARG, "stamps must not be NULL");
+    HIP_TRY(hipMemcpyAsync(c->T, stamps, c->S * c->W * sizeof(uint32_t), hipMemcpyDeviceToDevice,
+                           static_cast<hipStream_t>(stream)));
+    c->g.store(g);
     return HPS_OK;
 }
 

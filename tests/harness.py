@@ -30,8 +30,10 @@ QUERY_DEDUP = False
 class DeviceCache:
     """numpy in / numpy out wrapper over the C ABI (one cache)."""
 
-    def __init__(self, capacity, ways, dim, concurrent_writers=None):
-        self.h = B.hps_cache_create(capacity, ways, dim)
+    def __init__(self, capacity, ways, dim, concurrent_writers=None, policy=0):
+        self.policy = policy
+        self.h = (B.hps_cache_create(capacity, ways, dim) if policy == 0
+                  else B.hps_cache_create_policy(capacity, ways, dim, policy))
         self.S, self.W, self.d = B.hps_cache_info(self.h)
         assert self.S * self.W == capacity and self.W == ways and self.d == dim
         cw = CONCURRENT_WRITERS if concurrent_writers is None else concurrent_writers
@@ -103,6 +105,17 @@ class DeviceCache:
         ctr = c.cpu().numpy().view(np.uint32)
         vals = v.view(torch.int32).cpu().numpy().view(np.uint32).reshape(self.S, self.W, self.d) if with_vals else None
         return keys, ctr, vals
+
+    def export_lru(self):
+        t = torch.empty(self.S * self.W, dtype=torch.int32, device="cuda")
+        g = B.hps_cache_export_lru(self.h, t)
+        torch.cuda.synchronize()
+        return t.cpu().numpy().view(np.uint32).reshape(self.S, self.W), g
+
+    def load_lru(self, stamps, g):
+        t = torch.from_numpy(np.ascontiguousarray(stamps, dtype=np.uint32).view(np.int32).reshape(-1)).cuda()
+        B.hps_cache_import_lru(self.h, t, g)
+        torch.cuda.synchronize()
 
     def load(self, keys, ctr, vals=None):
         k = torch.from_numpy(np.ascontiguousarray(keys, dtype=np.int64).reshape(-1)).cuda()

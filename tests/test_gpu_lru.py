@@ -1,0 +1,176 @@
+"""GPU parity for the LRU replacement policy (the paper's rule) against the oracle's policy 1.
+
+Query results, miss lists and the access stamps after a query are unique and compared exactly.
+An insert batch has an order-independent result when, in every set, its new keys take slots that
+are empty or strictly older than the current iteration count and hold no key of the same batch;
+such batches are compared canonically (per set: keys sorted, each with its row and stamp), others
+by invariants.  As with the victim counter, which of the freed ways a new key lands in is arrival
+order, so after each insert the oracle adopts the GPU's placement.
+"""
+import collections
+
+import numpy as np
+import pytest
+
+from oracle import OracleCache
+from paper_2210_08804_amd import inputs
+from harness import DeviceCache, EMPTY_KEY, RESERVED_KEY, SENTINEL, check_state_invariants
+
+pytestmark = pytest.mark.gpu
+LRU = 1
+
+
+def rows_u32(keys, d, version=0):
+    return inputs.backing_rows(keys, d, version).view(np.uint32)
+
+
+def canon(keys, vals, stamps):
+    order = np.argsort(keys, axis=1, kind="stable")
+    return (np.take_along_axis(keys, order, axis=1), np.take_along_axis(vals, order[:, :, None], axis=1),
+            np.take_along_axis(stamps, order, axis=1))
+
+
+def assert_same(gc, oc):
+    gk, gctr, gv = gc.export()
+    gt, gg = gc.export_lru()
+    assert gg == oc.g
+    assert (gctr == np.array(oc.ctr)).all()
+    ck, cv, ct = canon(gk, gv, gt)
+    ok, ov, ot = canon(np.array(oc.keys), np.array(oc.vals), np.array(oc.stamps))
+    assert (ck == ok).all(), "resident key sets differ"
+    occ = ck != EMPTY_KEY
+    assert (cv[occ] == ov[occ]).all(), "rows differ"
+    assert (ct[occ] == ot[occ]).all(), "access stamps differ"
+    return gk, gctr, gv, gt
+
+
+def lru_insert_is_order_independent(oc, keys):
+    W, g = oc.W, oc.g
+    resident = set(np.array(oc.keys).reshape(-1).tolist())
+    batch = set(np.asarray(keys).tolist())
+    new = [k for k in batch - resident if k not in (EMPTY_KEY, RESERVED_KEY)]
+    per_set = collections.Counter(oc.set_of(k) for k in new)
+    for s, cnt in per_set.items():
+        if cnt > W:
+            return False
+        slots = []
+        for w in range(W):
+            k = int(oc.keys[s, w])
+            age = (g - int(oc.stamps[s, w])) % (1 << 32)
+            slots.append((0 if k == EMPTY_KEY else 1, -age, w, k, age))
+        slots.sort()
+        for empty_flag, _, w, k, age in slots[:cnt]:
+            if empty_flag == 1 and (age == 0 or k in batch):
+                return False
+    return True
+
+
+def query_both(gc, oc, keys):
+    out_g, mi_g, mk_g = gc.query(keys)
+    out_o = np.full((len(keys), oc.d), SENTINEL, dtype=np.uint32)
+    _, mi_o, mk_o = oc.query(keys, out_o)
+    assert (mi_g == mi_o).all() and (mk_g == mk_o).all() and (out_g == out_o).all()
+    return mi_o, mk_o
+
+
+def insert_both(gc, oc, keys, rows):
+    exact = lru_insert_is_order_independent(oc, keys)
+    gc.insert(keys, rows)
+    oc.insert(keys, rows)
+    if exact:
+        gk, gctr, gv, gt = assert_same(gc, oc)
+    else:
+        gk, gctr, gv = gc.export()
+        gt, _ = gc.export_lru()
+        check_state_invariants(gk, gctr, gv, oc.set_of)
+    oc.load_state(gk, gctr, gv, stamps=gt)
+    return exact
+
+
+@pytest.mark.parametrize("S,W,d,variant", [(64, 8, 16, "checked"), (97, 4, 8, "plain"), (5, 64, 4, "checked"),
+                                           (300, 8, 128, "plain"), (300, 8, 128, "dedup")])
+def test_lru_lookup_fill_loop_matches_oracle(S, W, d, variant):
+    import harness
+    from paper_2210_08804_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(S * 7 + W))
+    with DeviceCache(S * W, W, d, concurrent_writers=(variant == "checked"), policy=LRU) as gc:
+        B.hps_cache_set_query_dedup(gc.h, variant == "dedup")
+        oc = OracleCache(S * W, W, d, policy=LRU)
+        n_exact = 0
+        for step in range(30):
+            keys = inputs.zipf_keys(int(rng.integers(1, max(3, S * W // 4))), 6 * S * W, 1.05, 1000 + step)
+            _, mk = query_both(gc, oc, keys)
+            assert_same(gc, oc)                                   # stamps after the query
+            if len(mk):
+                n_exact += insert_both(gc, oc, mk, rows_u32(mk, d))
+            if step % 7 == 3:
+                uk = np.unique(keys)
+                gc.update(uk, rows_u32(uk, d, step))
+                oc.update(uk, rows_u32(uk, d, step))
+                assert_same(gc, oc)                               # update leaves stamps alone
+        assert n_exact >= 8, n_exact
+        query_both(gc, oc, np.arange(6 * S * W, dtype=np.int64))
+
+
+def test_lru_single_key_calls_are_textbook_lru_on_the_gpu():
+    W, d = 8, 16
+    with DeviceCache(W, W, d, policy=LRU) as gc:
+        lru = collections.OrderedDict()
+        rng = np.random.Generator(np.random.PCG64(3))
+        for _ in range(250):
+            k = int(rng.integers(0, 20))
+            key = np.array([k], dtype=np.int64)
+            _, mi, _ = gc.query(key)
+            assert (mi.size == 0) == (k in lru)
+            if k in lru:
+                lru.move_to_end(k)
+            else:
+                gc.insert(key, rows_u32(key, d))
+                if len(lru) == W:
+                    lru.popitem(last=False)
+                lru[k] = True
+        gk, _, _ = gc.export()
+        assert sorted(gk[gk != EMPTY_KEY].tolist()) == sorted(lru)
+
+
+def test_lru_keeps_the_hot_set_better_than_insertion_order():
+    """Streaming Zipf lookups with miss fill: recency-based replacement keeps hot keys that
+    insertion-order replacement throws out, so its hit rate is at least as high."""
+    S, W, d, n = 1 << 10, 8, 16, 20000
+    rates = {}
+    for policy in (0, LRU):
+        with DeviceCache(S * W, W, d, concurrent_writers=False, policy=policy) as gc:
+            hits = 0
+            for step in range(25):
+                keys = inputs.zipf_keys(n, 200000, 1.1, step + 1)
+                _, mi, mk = gc.query(keys)
+                if step >= 10:
+                    hits += n - len(mi)
+                if len(mk):
+                    uk = np.unique(mk)
+                    gc.insert(uk, rows_u32(uk, d))
+            rates[policy] = hits / (15 * n)
+    assert rates[LRU] > rates[0] + 0.005, rates
+
+
+def test_lru_export_import_and_wrong_policy_calls():
+    from paper_2210_08804_amd import binding as B
+    import torch
+    with DeviceCache(64, 8, 16, policy=LRU) as gc:
+        oc = OracleCache(64, 8, 16, policy=LRU)
+        oc.g = (1 << 32) - 3                                   # run across the 32-bit wrap
+        gc.load_lru(np.zeros((8, 8), dtype=np.uint32), oc.g)
+        for step in range(12):
+            keys = np.arange(step * 5, step * 5 + 30, dtype=np.int64)
+            _, mk = query_both(gc, oc, keys)
+            if len(mk):
+                insert_both(gc, oc, mk, rows_u32(mk, 16))
+        assert oc.g == 9
+    with DeviceCache(64, 8, 16, policy=0) as gc:
+        t = torch.zeros(64, dtype=torch.int32, device="cuda")
+        with pytest.raises(B.HpsError):
+            B.hps_cache_export_lru(gc.h, t)
+        with pytest.raises(B.HpsError):
+            B.hps_cache_import_lru(gc.h, t, 0)
+    with pytest.raises(B.HpsError):
+        B.hps_cache_create_policy(64, 8, 16, 7)
