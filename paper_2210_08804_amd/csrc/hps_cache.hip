@@ -432,7 +432,10 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 s_mkey[wave][r] = key;
             }
             if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(missmask);
-            if (tb.T && hit) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);   // Alg. 2: refresh the counter
+            // Alg. 2: refresh the counter.  A plain store: the XCD's write-back L2 merges the many stores
+            // a hot key draws (an agent-scope store per hit serialises them at the memory side and
+            // triples the kernel time); they reach memory at the latest when the kernel ends.
+            if (tb.T && hit) tb.T[(uint64_t)set * W + (uint32_t)way] = tb.g;
 
             if (kCoherent) {
                 __syncthreads();                           // rows were copied inside the retry loop
@@ -544,7 +547,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
             const uint32_t rep = is_rep ? tid : (want ? h_own[my] : tid);
             const int way = probe_wave<W, kWave>(tb.K, key, set, is_rep);
             if (is_rep) r_slot[tid] = way >= 0 ? (uint64_t)set * W + (uint32_t)way : kMissed;
-            if (tb.T && is_rep && way >= 0) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);
+            if (tb.T && is_rep && way >= 0) tb.T[(uint64_t)set * W + (uint32_t)way] = tb.g;
             __syncthreads();                                    // #3 probe results visible
             const uint64_t res = want ? r_slot[rep] : kMissed;
             const bool hit = res != kMissed;
