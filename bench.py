@@ -50,7 +50,7 @@ def parse():
     p.add_argument("--coherent", type=int, default=0,
                    help="1: queries validate rows against concurrent writers (not needed for a query-only run)")
     p.add_argument("--graph", type=int, default=0, help="1: replay the timed launches from one HIP graph")
-    p.add_argument("--streams", type=int, default=4,
+    p.add_argument("--streams", type=int, default=3,
                    help="also time the same batches issued round-robin over this many streams (0: skip)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-batches", type=int, default=100)
@@ -314,7 +314,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-            "kernel": "query_kernel<8,U>", "algorithmic_bytes_per_launch": round(alg_bytes),
+            "kernel": f"query_kernel<ways={W}, checked={bool(a.coherent)}>", "algorithmic_bytes_per_launch": round(alg_bytes),
             "us_per_launch": round(ms_per_step * 1e3, 3),
         },
     }
