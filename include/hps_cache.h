@@ -139,6 +139,22 @@ hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *cache, int enabled);
  */
 hps_status_t hps_cache_set_query_dedup(hps_cache_t *cache, int enabled);
 
+/*
+ * Flag word of a cache, raised by kernels (not a paper call; for callers that cannot tolerate a
+ * silent skip).  HPS_FLAG_STUCK_SET: a kernel waited about a second for a set that a writer never
+ * released (the writer's kernel must have died) and gave up: the query reported the affected keys
+ * as misses, insert/update skipped them.  *flags [host] receives the bits; clear != 0 resets them.
+ * Synchronous on the host; call it after synchronising the streams whose work is to be covered.
+ */
+#define HPS_FLAG_STUCK_SET 1u
+hps_status_t hps_cache_flags(hps_cache_t *cache, uint32_t *flags, int clear);
+
+/*
+ * Test hook: overwrite the sequence word of one set (host-synchronous).  An odd value imitates
+ * a writer that died while holding the set, which is how the bounded waits are tested.
+ */
+hps_status_t hps_cache_debug_set_seq(hps_cache_t *cache, uint64_t set, uint32_t value);
+
 /* Geometry of a cache.  Any output pointer [host] may be NULL. */
 hps_status_t hps_cache_info(const hps_cache_t *cache, uint64_t *num_sets, uint32_t *ways,
                             uint32_t *dim);

@@ -20,6 +20,7 @@ HPS_ERR_DEVICE = -3
 HPS_MAX_TABLES = 32
 HPS_POLICY_VICTIM_COUNTER = 0
 HPS_POLICY_LRU = 1
+HPS_FLAG_STUCK_SET = 1
 
 EXPORTS = (
     "hps_cache_create", "hps_cache_destroy", "hps_cache_query", "hps_cache_insert",
@@ -27,6 +28,7 @@ EXPORTS = (
     "hps_cache_export", "hps_cache_import", "hps_cache_dump", "hps_cache_query_multi",
     "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn", "hps_cache_set_query_dedup",
     "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
+    "hps_cache_flags", "hps_cache_debug_set_seq",
 )
 
 _lib = None
@@ -56,6 +58,8 @@ def load_library():
         "hps_cache_create_policy": [sz, u32, u32, C.c_int, C.POINTER(vp)],
         "hps_cache_export_lru": [vp, vp, C.POINTER(u32), vp],
         "hps_cache_import_lru": [vp, vp, u32, vp],
+        "hps_cache_flags": [vp, C.POINTER(u32), C.c_int],
+        "hps_cache_debug_set_seq": [vp, C.c_uint64, u32],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
         "hps_cache_insert": [vp, vp, vp, sz, vp],
@@ -121,6 +125,16 @@ def hps_cache_export_lru(handle, stamps, stream=None) -> int:
 
 def hps_cache_import_lru(handle, stamps, g: int, stream=None) -> None:
     _check(load_library().hps_cache_import_lru(handle, _ptr(stamps, torch.int32), g, _stream(stream)))
+
+
+def hps_cache_flags(handle, clear: bool = False) -> int:
+    f = C.c_uint32()
+    _check(load_library().hps_cache_flags(handle, C.byref(f), 1 if clear else 0))
+    return f.value
+
+
+def hps_cache_debug_set_seq(handle, set_index: int, value: int) -> None:
+    _check(load_library().hps_cache_debug_set_seq(handle, set_index, value))
 
 
 def hps_cache_destroy(handle) -> None:

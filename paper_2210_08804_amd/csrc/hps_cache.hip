@@ -32,6 +32,10 @@ constexpr int      kWave       = 64;
 constexpr int      kWavesPerWg = kBlock / kWave;
 constexpr uint32_t kRing       = 1024;         // per-call counter slots (see QueryArgs::slot)
 constexpr uint64_t kMagic      = 0x4850534341434845ull;
+// Every loop that waits for another kernel's writer to let go of a set gives up after this many
+// rounds (a held set is released within microseconds; this many rounds take about a second) and
+// raises HPS_FLAG_STUCK_SET in the cache's flag word, so that no wave can spin forever.
+constexpr uint32_t kMaxRounds  = 1u << 16;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk of a row
 
@@ -146,6 +150,7 @@ struct Table {                 // one cache as the kernels see it
     uint32_t  smask;           // S - 1 when S is a power of two, else 0
     uint32_t *T;               // [S][W] access stamps, LRU policy only (else nullptr)
     uint32_t  g;               // the call's global iteration count (LRU policy)
+    uint32_t *flags;           // one word of HPS_FLAG_* bits raised by kernels
 };
 
 // Row geometry shared by all copy loops: a row is C = d/4 chunks of 16 bytes; LPR lanes
@@ -390,7 +395,13 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 hit = false;
                 way = -1;
                 bool pending = want;
+                uint32_t rounds = 0;
                 while (__ballot(pending)) {
+                    if (++rounds > kMaxRounds) {                     // a set never came free: report a miss
+                        if (pending) __hip_atomic_fetch_or(tb.flags, (uint32_t)HPS_FLAG_STUCK_SET, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
                     const uint32_t v1 = pending ? ld_agent(tb.seq + set) : 0u;
                     const bool busy = pending && (v1 & 1u);          // a writer holds the set: look again later
                     shared_acquire();                                // the word is read before any key or row
@@ -673,7 +684,13 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
         bool pending = i < n && !is_reserved(key);
         const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
 
+        uint32_t rounds = 0;
         while (__ballot(pending)) {
+            if (++rounds > kMaxRounds) {                             // a set never came free: skip these keys
+                if (pending) __hip_atomic_fetch_or(tb.flags, (uint32_t)HPS_FLAG_STUCK_SET, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
             bool won = false;
             uint32_t v = 0;
             int way = -1;
@@ -772,7 +789,13 @@ __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
         bool pending = i < n && !is_reserved(key);
         const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
 
+        uint32_t rounds = 0;
         while (const uint64_t pendmask = __ballot(pending)) {
+            if (++rounds > kMaxRounds) {                             // a set never came free: skip these keys
+                if (pending) __hip_atomic_fetch_or(tb.flags, (uint32_t)HPS_FLAG_STUCK_SET, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
             // groups: maximal runs of adjacent pending lanes with equal set
             const uint32_t prev_set = (uint32_t)__shfl_up((int)set, 1, kWave);
             const int prev_pend = __shfl_up((int)pending, 1, kWave);
@@ -977,6 +1000,7 @@ struct hps_cache {
     int      policy;                      // HPS_POLICY_*
     uint32_t *T;                          // access stamps (LRU policy), else nullptr
     std::atomic<uint32_t> g;              // global iteration count: one step per query call (LRU policy)
+    uint32_t *flags;                      // device word of HPS_FLAG_* bits
 };
 
 namespace {
@@ -1002,6 +1026,7 @@ Table table_of(const hps_cache *c) {
     if (c->S == 1) t.smask = 0;           // S = 1: "h % 1" = 0 (a zero mask means "use modulo")
     t.T = c->T;
     t.g = c->g.load(std::memory_order_relaxed);
+    t.flags = c->flags;
     return t;
 }
 
@@ -1142,7 +1167,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->S = capacity / ways;
     c->W = ways;
     c->d = dim;
-    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr;
+    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr;
     c->policy = policy;
     c->g.store(0);
     c->calls.store(0);
@@ -1155,6 +1180,8 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     if (e == hipSuccess) e = hipMalloc(&c->ctr, c->S * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->seq, c->S * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->ring, kRing * sizeof(uint64_t));
+    if (e == hipSuccess) e = hipMalloc(&c->flags, sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemsetAsync(c->flags, 0, sizeof(uint32_t), 0);
     if (e == hipSuccess && policy == HPS_POLICY_LRU) {
         e = hipMalloc(&c->T, capacity * sizeof(uint32_t));
         if (e == hipSuccess) e = hipMemsetAsync(c->T, 0, capacity * sizeof(uint32_t), 0);
@@ -1178,6 +1205,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
         if (c->seq) (void)hipFree(c->seq);
         if (c->ring) (void)hipFree(c->ring);
         if (c->T) (void)hipFree(c->T);
+        if (c->flags) (void)hipFree(c->flags);
         delete c;
         return fail(code, msg);
     }
@@ -1195,6 +1223,7 @@ hps_status_t hps_cache_destroy(hps_cache_t *c) {
     if ((e2 = hipFree(c->seq)) != hipSuccess) e = e2;
     if ((e2 = hipFree(c->ring)) != hipSuccess) e = e2;
     if (c->T && (e2 = hipFree(c->T)) != hipSuccess) e = e2;
+    if ((e2 = hipFree(c->flags)) != hipSuccess) e = e2;
     delete c;
     if (e != hipSuccess) return fail(HPS_ERR_DEVICE, std::string("hipFree: ") + hipGetErrorString(e));
     return HPS_OK;
@@ -1211,6 +1240,21 @@ hps_status_t hps_cache_info(const hps_cache_t *c, uint64_t *num_sets, uint32_t *
 hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *c, int enabled) {
     if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
     c->concurrent_writers.store(enabled ? 1 : 0);
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_flags(hps_cache_t *c, uint32_t *flags, int clear) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (!flags) return fail(HPS_ERR_INVALID_ARG, "flags is NULL");
+    HIP_TRY(hipMemcpy(flags, c->flags, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    if (clear) HIP_TRY(hipMemset(c->flags, 0, sizeof(uint32_t)));
+    return HPS_OK;
+}
+
+hps_status_t hps_cache_debug_set_seq(hps_cache_t *c, uint64_t set, uint32_t value) {
+    if (hps_status_t s = check_handle(c)) return s;
+    if (set >= c->S) return fail(HPS_ERR_INVALID_ARG, "set index out of range");
+    HIP_TRY(hipMemcpy(c->seq + set, &value, sizeof(uint32_t), hipMemcpyHostToDevice));
     return HPS_OK;
 }
 
