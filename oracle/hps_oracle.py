@@ -17,12 +17,13 @@ RESERVED_KEY = -(1 << 63) + 1   # second reserved value of the build's contract
 _lib = None
 
 
-def _load():
+def load_library(path=None):
+    """Load the oracle library.  `path` names another build of it (the mutation tests compile
+    deliberately broken copies); the default is the library built from oracle/hps_oracle.c."""
     global _lib
-    if _lib is not None:
+    if path is None and _lib is not None:
         return _lib
-    path = _build.build()
-    lib = C.CDLL(path)
+    lib = C.CDLL(path if path is not None else _build.build())
     vp, u64, u32 = C.c_void_p, C.c_uint64, C.c_uint32
     lib.hpso_mix64.restype = u64
     lib.hpso_mix64.argtypes = [u64]
@@ -51,12 +52,17 @@ def _load():
     lib.hpso_update.argtypes = [vp, vp, vp, u64]
     lib.hpso_dump.restype = u64
     lib.hpso_dump.argtypes = [vp, vp]
-    _lib = lib
+    if path is None:
+        _lib = lib
     return lib
 
 
-def mix64(x: int) -> int:
-    return int(_load().hpso_mix64(C.c_uint64(x & 0xFFFFFFFFFFFFFFFF)))
+def _load():
+    return load_library()
+
+
+def mix64(x: int, lib=None) -> int:
+    return int((lib or _load()).hpso_mix64(C.c_uint64(x & 0xFFFFFFFFFFFFFFFF)))
 
 
 def _keys(a):
@@ -78,9 +84,9 @@ def _rows(a, n, d):
 class OracleCache:
     """One set-associative cache of `capacity` slots, `ways` slots per set, `dim` words per row."""
 
-    def __init__(self, capacity: int, ways: int, dim: int, policy: int = 0):
+    def __init__(self, capacity: int, ways: int, dim: int, policy: int = 0, lib=None):
         """policy 0: per-set victim counter; policy 1: LRU by access stamp (the paper's rule)."""
-        lib = _load()
+        lib = lib or _load()
         self._lib = lib
         self.policy = policy
         self._h = lib.hpso_create_policy(capacity, ways, dim, policy)
@@ -165,6 +171,6 @@ class OracleCache:
             self.vals[...] = v.reshape(self.S, self.W, self.d)
 
 
-def set_of(key: int, num_sets: int) -> int:
+def set_of(key: int, num_sets: int, lib=None) -> int:
     """Set index of a key for a cache with `num_sets` sets (same rule as the C file, via its mix64)."""
-    return (mix64(key) >> 32) % num_sets
+    return (mix64(key, lib) >> 32) % num_sets
