@@ -28,9 +28,11 @@ METRIC = "cache query Mkeys/s + achieved HBM GB/s (dim 128 fp32, Zipf keys)"
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--workload", choices=["query", "refresh"], default="query",
+    p.add_argument("--workload", choices=["query", "refresh", "stream", "multi", "concurrent"], default="query",
                    help="query: the headline hot-cache query (default); refresh: dump every cached key, then "
-                        "update every cached row (the cache refresh of the paper's Table 3)")
+                        "update every cached row (the paper's Table 3); stream: query + miss fill + insert per "
+                        "step on a cold cache; multi: 26 tables in one launch; concurrent: queries on one "
+                        "stream while updates run on another")
     p.add_argument("--capacity-gb", type=float, default=10.0, help="refresh: bytes of rows in the cache")
     p.add_argument("--policy", choices=["counter", "lru"], default="counter",
                    help="replacement policy of the cache: per-set victim counter (default) or the paper's LRU stamps")
@@ -137,6 +139,163 @@ def refresh(a, np, torch, B):
     print(json.dumps(res))
 
 
+def _prefill_descending(B, torch, h, n_ids, d, chunk=1 << 20):
+    """Insert ids n_ids-1 .. 0 (hottest last) with rows from the device-side backing stand-in."""
+    ids = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    rows = torch.empty(chunk, d, dtype=torch.float32, device="cuda")
+    for hi in range(n_ids, 0, -chunk):
+        lo = max(0, hi - chunk)
+        m = hi - lo
+        ids[:m] = torch.arange(hi - 1, lo - 1, -1, dtype=torch.int64, device="cuda")
+        B.hps_backing_fetch(ids, m, d, version=0, rows=rows)
+        B.hps_cache_insert(h, ids, rows, m)
+    torch.cuda.synchronize()
+
+
+def stream_fill(a, np, torch, B, inputs):
+    """Streaming query + miss fill (Alg. 1, synchronous branch, all on the device): per step query
+    16384 x 26 Zipf(1.1) keys, fetch the missing rows from the backing stand-in into `out` and a
+    compact buffer, insert them.  Cold start; the hit rate per step shows the warm-up."""
+    S, W, d = 1 << 20, 8, a.dim
+    n = 16384 * 26
+    steps = min(a.steps, 500)
+    h = (B.hps_cache_create(S * W, W, d) if a.policy == "counter"
+         else B.hps_cache_create_policy(S * W, W, d, B.HPS_POLICY_LRU))
+    B.hps_cache_set_concurrent_writers(h, False)
+    keys = [torch.from_numpy(inputs.zipf_keys(n, 10 ** 8, 1.1, s + 1)).cuda() for s in range(steps)]
+    out = torch.empty(n, d, dtype=torch.float32, device="cuda")
+    rows = torch.empty(n, d, dtype=torch.float32, device="cuda")
+    mi = torch.empty(n, dtype=torch.int32, device="cuda")
+    mk = torch.empty(n, dtype=torch.int64, device="cuda")
+    nm = torch.zeros(steps, dtype=torch.int32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for s in range(steps):
+        B.hps_cache_query(h, keys[s], n, out, mi, mk, nm[s:s + 1])
+        B.hps_backing_fetch(mk, n, d, version=0, rows=rows, n_dev=nm[s:s + 1], scatter_idx=mi, scatter_out=out)
+        B.hps_cache_insert_dn(h, mk, rows, n, nm[s:s + 1])
+        ev[s + 1].record()
+    torch.cuda.synchronize()
+    ms = np.array([ev[s].elapsed_time(ev[s + 1]) for s in range(steps)])
+    hit = 1.0 - nm.cpu().numpy() / n
+    tail = slice(steps // 2, steps)
+    res = {"metric": "streaming lookup Mkeys/s (query + miss fill + insert per step)", "value": round(n / (ms[tail].mean() * 1e-3) / 1e6, 1),
+           "unit": "Mkeys/s", "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": round(float(ms[tail].mean()), 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"streaming query + miss fill: {S} sets x {W} ways, dim {d}, {n} Zipf(1.1) keys over 1e8 per step, cold start",
+                      "replacement_policy": a.policy,
+                      "hit_rate_per_step": [round(float(x), 4) for x in hit[: 10]] + ["..."] + [round(float(x), 4) for x in hit[-5:]],
+                      "ms_per_step_first10": [round(float(x), 3) for x in ms[:10]]}}
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    print(json.dumps(res))
+
+
+def multi_table(a, np, torch, B, inputs):
+    """26 independent caches (vocabulary log-uniform in [1e3, 1e8], each cache 20 % of its vocabulary,
+    at most 2^22 slots), one Zipf(1.05) key per table and sample, 131072 samples, one launch."""
+    W, d, Bn = 8, a.dim, 131072
+    vocab = inputs.log_uniform_vocab(26, 1e3, 1e8, 7)
+    slots = [int(min(0.2 * v, 1 << 22)) // 8 * 8 for v in vocab]
+    hs = []
+    for s in slots:
+        h = B.hps_cache_create(s, W, d)
+        B.hps_cache_set_concurrent_writers(h, False)
+        _prefill_descending(B, torch, h, s, d, chunk=1 << 18)
+        hs.append(h)
+    n = 26 * Bn
+    nb = 8
+    keys = [torch.from_numpy(np.stack([inputs.zipf_keys(Bn, int(v), 1.05, 7 + 1000 * t + 100000 * b)
+                                       for t, v in enumerate(vocab)])).cuda() for b in range(nb)]
+    outs = [torch.empty(n, d, dtype=torch.float32, device="cuda") for _ in range(2)]
+    mi = torch.empty(n, dtype=torch.int32, device="cuda")
+    mk = torch.empty(n, dtype=torch.int64, device="cuda")
+    nm = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    for b in range(nb):
+        B.hps_cache_query_multi(hs, keys[b], Bn, outs[b % 2], mi, mk, nm[b:b + 1])
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(1, a.steps // nb)
+    e0.record()
+    for r in range(reps):
+        for b in range(nb):
+            B.hps_cache_query_multi(hs, keys[b], Bn, outs[b % 2], mi, mk, nm[b:b + 1])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (reps * nb)
+    hit = 1.0 - float(nm.cpu().numpy().mean()) / n
+    alg = 8 * n + (64 + 4 * d) * n * hit * 0.5 + 4 * d * n * hit          # rough: half of the hit keys distinct
+    res = {"metric": "multi-table lookup Mkeys/s (26 tables, one launch)", "value": round(n / (ms * 1e-3) / 1e6, 1),
+           "unit": "Mkeys/s", "n_gpus": 1, "steps": reps * nb, "warmup": nb, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"26 caches, slots {min(slots)}..{max(slots)} (total {sum(slots)}), dim {d}, batch {Bn} samples x 26 keys",
+                      "hit_rate": round(hit, 4), "out_write_GBps": round(n * hit * 4 * d / (ms * 1e-3) / 1e9, 1)}}
+    torch.cuda.synchronize()
+    for h in hs:
+        B.hps_cache_destroy(h)
+    print(json.dumps(res))
+
+
+def concurrent(a, np, torch, B, inputs):
+    """Online update concurrent with query: 2^24 sets x 8 ways x dim (64 GiB at dim 128); queries of
+    65536 x 26 Zipf(1.05) keys over 1e9 ids on one stream, updates of 262144 <key, row> pairs (half
+    of the keys cached) on a second stream; both rates are reported, alone and overlapped."""
+    S, W, d = 1 << 24, 8, a.dim
+    n_q, n_u = 65536 * 26, 262144
+    h = B.hps_cache_create(S * W, W, d)
+    B.hps_cache_set_concurrent_writers(h, True)
+    _prefill_descending(B, torch, h, S * W, d)
+    nb = 6
+    rng = np.random.Generator(np.random.PCG64(5))
+    qk = [torch.from_numpy(inputs.zipf_keys(n_q, 10 ** 9, 1.05, 100 + b)).cuda() for b in range(nb)]
+    uk = [torch.from_numpy(np.concatenate([rng.integers(0, S * W, n_u // 2), rng.integers(2 * 10 ** 9, 3 * 10 ** 9, n_u // 2)])
+                           .astype(np.int64)).cuda() for b in range(nb)]
+    urows = torch.empty(n_u, d, dtype=torch.float32, device="cuda")
+    B.hps_backing_fetch(uk[0], n_u, d, version=1, rows=urows)
+    outs = [torch.empty(n_q, d, dtype=torch.float32, device="cuda") for _ in range(2)]
+    mi = torch.empty(n_q, dtype=torch.int32, device="cuda")
+    mk = torch.empty(n_q, dtype=torch.int64, device="cuda")
+    nm = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    qs, us = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    def run(do_q, do_u, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        qs.wait_stream(torch.cuda.current_stream())
+        us.wait_stream(torch.cuda.current_stream())
+        for r in range(reps):
+            for b in range(nb):
+                if do_q:
+                    B.hps_cache_query(h, qk[b], n_q, outs[b % 2], mi, mk, nm[b:b + 1], qs)
+                if do_u:
+                    for _ in range(2):
+                        B.hps_cache_update(h, uk[b], urows, n_u, us)
+        torch.cuda.current_stream().wait_stream(qs)
+        torch.cuda.current_stream().wait_stream(us)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * nb)
+
+    run(True, True, 1)
+    reps = max(1, a.steps // nb)
+    q_alone, u_alone, both = run(True, False, reps), run(False, True, reps) / 2, run(True, True, reps)
+    hit = 1.0 - float(nm.cpu().numpy().mean()) / n_q
+    res = {"metric": "query Mkeys/s while updates run on a second stream", "value": round(n_q / (both * 1e-3) / 1e6, 1),
+           "unit": "Mkeys/s", "n_gpus": 1, "steps": reps * nb, "warmup": nb, "ms_per_step": round(both, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"{S} sets x {W} ways, dim {d}; query {n_q} Zipf(1.05) keys over 1e9; 2 update batches of {n_u} pairs per query batch",
+                      "hit_rate": round(hit, 4), "query_alone_ms": round(q_alone, 4), "update_batch_alone_ms": round(u_alone, 4),
+                      "query_plus_2_updates_overlapped_ms": round(both, 4),
+                      "query_alone_Mkeys_s": round(n_q / (q_alone * 1e-3) / 1e6, 1),
+                      "update_alone_Mpairs_s": round(n_u / (u_alone * 1e-3) / 1e6, 1)}}
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -154,6 +313,12 @@ def main():
     lib = B.load_library()
     if a.workload == "refresh":
         return refresh(a, np, torch, B)
+    if a.workload == "stream":
+        return stream_fill(a, np, torch, B, inputs)
+    if a.workload == "multi":
+        return multi_table(a, np, torch, B, inputs)
+    if a.workload == "concurrent":
+        return concurrent(a, np, torch, B, inputs)
 
     S, W, d = 1 << a.log2_sets, a.ways, a.dim
     slots = S * W
