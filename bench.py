@@ -300,7 +300,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {a.gpus}); "
-              "each GPU would hold an independent cache, see DESIGN.md", file=sys.stderr)
+              "with more GPUs each one would hold its own independent cache", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
