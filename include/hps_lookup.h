@@ -1,0 +1,68 @@
+/*
+ * hps_lookup.h — Algorithm 1 of the paper ("Embedding cache insertion", Sec. 3.1 / Sec. 4.3) on top
+ * of the GPU embedding cache of hps_cache.h: look the batch up in the cache, compute the hit rate,
+ * and either fetch and insert the missing rows at once (synchronous insertion, hit rate below the
+ * threshold) or hand out the default vector for them now and fetch and insert them in the
+ * background (asynchronous insertion).
+ *
+ * The lower storage tiers (Sec. 5) are the caller's: a fetch callback that receives the missing
+ * keys in host memory and fills their rows in host memory.  Everything else runs on the device.
+ * One lookup object serves one stream of batches (it owns one workspace, the paper's `ws`); use
+ * one object per concurrent inference worker, all on the same cache.
+ */
+#ifndef HPS_LOOKUP_H
+#define HPS_LOOKUP_H
+
+#include "hps_cache.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hps_lookup_session hps_lookup_t;
+
+/*
+ * Lower-tier fetch: write the row of keys[i] to rows[i*dim .. i*dim+dim) for i < n.  keys and rows
+ * are host pointers (pinned, owned by the lookup object); keys are distinct.  Called on the thread
+ * that calls hps_lookup (synchronous insertion) or on the object's background thread.
+ */
+typedef void (*hps_fetch_fn)(void *user, const int64_t *keys, size_t n, float *rows);
+
+/*
+ * cache           the cache to serve from; it must allow concurrent writers
+ *                 (hps_cache_set_concurrent_writers(cache, 1), the default) because background
+ *                 inserts overlap later queries.
+ * max_batch       largest n a lookup call may pass.
+ * hit_threshold   t of Alg. 1: hit rate < t selects synchronous insertion.  0 = always
+ *                 asynchronous, anything above 1 = always synchronous.
+ * default_row     [host, dim fp32] vector handed out for missing keys in asynchronous mode.
+ * Errors: INVALID_ARG, OOM, DEVICE.
+ */
+hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_threshold,
+                               const float *default_row, hps_fetch_fn fetch, void *user,
+                               hps_lookup_t **out_lookup);
+
+/*
+ * One pass of Alg. 1.  keys [device, n int64], out [device, n*dim fp32], stream as in hps_cache.h.
+ * Hit rate = 1 - misses / n per position (Alg. 1 prints "/ N = total size of embedding cache",
+ * which cannot be meant).  On return every row of out is either its key's cached row, its fetched
+ * row (synchronous mode) or the default row (asynchronous mode), in stream order: the call
+ * synchronises the host with `stream` once, to read the miss count, as Alg. 1 needs it.
+ * *hit_rate [host] and *was_synchronous [host] may be NULL.
+ */
+hps_status_t hps_lookup(hps_lookup_t *lookup, const int64_t *keys, size_t n, float *out,
+                        float *hit_rate, int *was_synchronous, void *stream);
+
+/* Block until every queued asynchronous insertion has been applied to the cache. */
+hps_status_t hps_lookup_drain(hps_lookup_t *lookup);
+
+/* Drains, then frees the object (not the cache). */
+hps_status_t hps_lookup_destroy(hps_lookup_t *lookup);
+
+/* Message for the last error of the hps_lookup_* calls on this thread. */
+const char *hps_lookup_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HPS_LOOKUP_H */

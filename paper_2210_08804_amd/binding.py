@@ -29,7 +29,11 @@ EXPORTS = (
     "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn", "hps_cache_set_query_dedup",
     "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
     "hps_cache_flags", "hps_cache_debug_set_seq",
+    "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
 )
+
+# lower-tier fetch callback of hps_lookup.h: (user, keys*, n, rows*)
+FETCH_FN = C.CFUNCTYPE(None, C.c_void_p, C.POINTER(C.c_int64), C.c_size_t, C.POINTER(C.c_float))
 
 _lib = None
 
@@ -53,6 +57,8 @@ def load_library():
     vp, sz, u32 = C.c_void_p, C.c_size_t, C.c_uint32
     lib.hps_last_error.restype = C.c_char_p
     lib.hps_last_error.argtypes = []
+    lib.hps_lookup_last_error.restype = C.c_char_p
+    lib.hps_lookup_last_error.argtypes = []
     sigs = {
         "hps_cache_create": [sz, u32, u32, C.POINTER(vp)],
         "hps_cache_create_policy": [sz, u32, u32, C.c_int, C.POINTER(vp)],
@@ -60,6 +66,10 @@ def load_library():
         "hps_cache_import_lru": [vp, vp, u32, vp],
         "hps_cache_flags": [vp, C.POINTER(u32), C.c_int],
         "hps_cache_debug_set_seq": [vp, C.c_uint64, u32],
+        "hps_lookup_create": [vp, sz, C.c_float, vp, FETCH_FN, vp, C.POINTER(vp)],
+        "hps_lookup": [vp, vp, sz, vp, C.POINTER(C.c_float), C.POINTER(C.c_int), vp],
+        "hps_lookup_drain": [vp],
+        "hps_lookup_destroy": [vp],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
         "hps_cache_insert": [vp, vp, vp, sz, vp],
@@ -219,3 +229,39 @@ def hps_backing_fetch(keys, n, dim, version=0, rows=None, n_dev=None, scatter_id
 
 def hps_last_error() -> str:
     return load_library().hps_last_error().decode()
+
+
+def _check_lookup(status):
+    if status != HPS_OK:
+        raise HpsError(status, load_library().hps_lookup_last_error().decode())
+
+
+def hps_lookup_last_error() -> str:
+    return load_library().hps_lookup_last_error().decode()
+
+
+def hps_lookup_create(cache, max_batch: int, hit_threshold: float, default_row, fetch) -> int:
+    """default_row: host float32 array of dim values; fetch: a FETCH_FN object, which the caller
+    must keep alive as long as the lookup object exists."""
+    import numpy as np
+    row = np.ascontiguousarray(default_row, dtype=np.float32)
+    h = C.c_void_p()
+    _check_lookup(load_library().hps_lookup_create(cache, max_batch, hit_threshold, row.ctypes.data, fetch, None,
+                                                   C.byref(h)))
+    return h.value
+
+
+def hps_lookup(lookup, keys, n, out, stream=None):
+    """Returns (hit_rate, was_synchronous)."""
+    rate, sync = C.c_float(), C.c_int()
+    _check_lookup(load_library().hps_lookup(lookup, _ptr(keys, torch.int64), n, _ptr(out, torch.float32),
+                                            C.byref(rate), C.byref(sync), _stream(stream)))
+    return rate.value, bool(sync.value)
+
+
+def hps_lookup_drain(lookup) -> None:
+    _check_lookup(load_library().hps_lookup_drain(lookup))
+
+
+def hps_lookup_destroy(lookup) -> None:
+    _check_lookup(load_library().hps_lookup_destroy(lookup))

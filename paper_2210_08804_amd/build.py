@@ -1,11 +1,11 @@
-"""Compile csrc/hps_cache.hip for gfx950 into paper_2210_08804_amd/libhps_cache.so (in-tree)."""
+"""Compile csrc/*.hip for gfx950 into paper_2210_08804_amd/libhps_cache.so (in-tree)."""
 import os
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "hps_cache.hip")
+SRCS = [os.path.join(HERE, "csrc", "hps_cache.hip"), os.path.join(HERE, "csrc", "hps_lookup.hip")]
 LIB = os.path.join(HERE, "libhps_cache.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -21,7 +21,7 @@ FLAGS = [
 
 
 def build(extra=()):
-    cmd = [HIPCC, *FLAGS, *extra, SRC, "-o", LIB]
+    cmd = [HIPCC, *FLAGS, *extra, *SRCS, "-o", LIB, "-lpthread"]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -1,0 +1,319 @@
+// Algorithm 1 of the paper (embedding cache insertion: hit-rate test, synchronous or asynchronous
+// fill) on top of the C ABI of the cache.  Host orchestration plus two small kernels; the lower
+// tiers are a caller-supplied fetch callback working on pinned host buffers.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <condition_variable>
+#include <cstdint>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <string>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "hps_lookup.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// out[idx[j]] = rows[src[j]] for j < m (src == nullptr: rows[0], the default vector).
+__global__ void place_rows_kernel(float *out, const uint32_t *__restrict__ idx,
+                                  const uint32_t *__restrict__ src, const float *__restrict__ rows,
+                                  uint32_t m, uint32_t d) {
+    const uint32_t C = d / 4;
+    const uint64_t total = (uint64_t)m * C;
+    for (uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; t < total;
+         t += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t j = (uint32_t)(t / C);
+        const uint32_t c = (uint32_t)(t - (uint64_t)j * C);
+        const uint64_t r = src ? src[j] : 0u;
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(rows + r * d + c * 4);
+        *reinterpret_cast<f32x4 *>(out + (uint64_t)idx[j] * d + c * 4) = v;
+    }
+}
+
+struct Task {                 // one queued asynchronous insertion
+    int64_t   *h_keys;        // pinned, the batch's missing keys (with duplicates)
+    uint32_t   m;
+    hipEvent_t ready;         // the device-to-host copy of h_keys has finished
+};
+
+}  // namespace
+
+struct hps_lookup_session {
+    hps_cache_t *cache;
+    int          device;
+    size_t       max_batch;
+    uint32_t     dim;
+    float        threshold;
+    hps_fetch_fn fetch;
+    void        *user;
+    // workspace (the paper's ws): device side
+    uint32_t *d_miss_idx, *d_n_miss, *d_inv;
+    int64_t  *d_miss_keys, *d_ukeys;
+    float    *d_rows, *d_default;
+    // pinned host side
+    uint32_t *h_n_miss, *h_inv;
+    int64_t  *h_keys, *h_ukeys;
+    float    *h_rows;
+    // background insertion
+    hipStream_t side;
+    int64_t  *bg_d_ukeys;
+    float    *bg_d_rows, *bg_h_rows;
+    int64_t  *bg_h_ukeys;
+    std::thread worker;
+    std::mutex mu;
+    std::condition_variable cv, cv_idle;
+    std::deque<Task> queue;
+    std::vector<int64_t *> free_key_bufs;
+    bool stop = false, busy = false;
+    std::string worker_error;
+};
+
+namespace {
+
+thread_local std::string g_lookup_err;
+
+hps_status_t lfail(hps_status_t code, const std::string &msg) {
+    g_lookup_err = msg;
+    return code;
+}
+
+#define LK_TRY(expr)                                                                         \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return lfail(e_ == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE,            \
+                         std::string(#expr) + ": " + hipGetErrorString(e_));                 \
+    } while (0)
+
+// Distinct keys of a miss list, in first-occurrence order, and for every entry the index of its
+// key among them (the paper deduplicates before going to the lower tiers, Sec. 2.2).
+uint32_t dedup_host(const int64_t *keys, uint32_t m, int64_t *ukeys, uint32_t *inv) {
+    std::unordered_map<int64_t, uint32_t> seen;
+    seen.reserve(m * 2);
+    uint32_t u = 0;
+    for (uint32_t j = 0; j < m; ++j) {
+        auto it = seen.find(keys[j]);
+        if (it == seen.end()) {
+            seen.emplace(keys[j], u);
+            ukeys[u] = keys[j];
+            if (inv) inv[j] = u;
+            ++u;
+        } else if (inv) {
+            inv[j] = it->second;
+        }
+    }
+    return u;
+}
+
+void launch_place(float *out, const uint32_t *idx, const uint32_t *src, const float *rows, uint32_t m,
+                  uint32_t d, hipStream_t st) {
+    const uint64_t total = (uint64_t)m * (d / 4);
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > (1u << 16)) blocks = 1u << 16;
+    hipLaunchKernelGGL(place_rows_kernel, dim3((uint32_t)blocks), dim3(256), 0, st, out, idx, src, rows, m, d);
+}
+
+// Background thread: the asyncInsert procedure of Alg. 1 (lower-tier lookup, then insert).
+void worker_main(hps_lookup_session *L) {
+    (void)hipSetDevice(L->device);
+    for (;;) {
+        Task t;
+        {
+            std::unique_lock<std::mutex> lk(L->mu);
+            L->cv.wait(lk, [&] { return L->stop || !L->queue.empty(); });
+            if (L->queue.empty()) return;                      // stop requested and nothing left
+            t = L->queue.front();
+            L->queue.pop_front();
+            L->busy = true;
+        }
+        std::string err;
+        hipError_t e = hipEventSynchronize(t.ready);
+        if (e == hipSuccess) {
+            const uint32_t u = dedup_host(t.h_keys, t.m, L->bg_h_ukeys, nullptr);
+            L->fetch(L->user, L->bg_h_ukeys, u, L->bg_h_rows);
+            e = hipMemcpyAsync(L->bg_d_ukeys, L->bg_h_ukeys, (size_t)u * sizeof(int64_t), hipMemcpyHostToDevice, L->side);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(L->bg_d_rows, L->bg_h_rows, (size_t)u * L->dim * sizeof(float),
+                                   hipMemcpyHostToDevice, L->side);
+            if (e == hipSuccess && hps_cache_insert(L->cache, L->bg_d_ukeys, L->bg_d_rows, u, L->side) != HPS_OK)
+                err = std::string("background insert: ") + hps_last_error();
+            if (e == hipSuccess) e = hipStreamSynchronize(L->side);
+        }
+        if (e != hipSuccess) err = std::string("background insertion: ") + hipGetErrorString(e);
+        (void)hipEventDestroy(t.ready);
+        {
+            std::lock_guard<std::mutex> lk(L->mu);
+            L->free_key_bufs.push_back(t.h_keys);
+            if (!err.empty()) L->worker_error = err;
+            L->busy = false;
+        }
+        L->cv_idle.notify_all();
+    }
+}
+
+void free_all(hps_lookup_session *L) {
+    (void)hipFree(L->d_miss_idx); (void)hipFree(L->d_n_miss); (void)hipFree(L->d_inv);
+    (void)hipFree(L->d_miss_keys); (void)hipFree(L->d_ukeys); (void)hipFree(L->d_rows); (void)hipFree(L->d_default);
+    (void)hipFree(L->bg_d_ukeys); (void)hipFree(L->bg_d_rows);
+    (void)hipHostFree(L->h_n_miss); (void)hipHostFree(L->h_inv); (void)hipHostFree(L->h_keys);
+    (void)hipHostFree(L->h_ukeys); (void)hipHostFree(L->h_rows); (void)hipHostFree(L->bg_h_rows);
+    (void)hipHostFree(L->bg_h_ukeys);
+    for (int64_t *p : L->free_key_bufs) (void)hipHostFree(p);
+    if (L->side) (void)hipStreamDestroy(L->side);
+}
+
+}  // namespace
+
+extern "C" {
+
+hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_threshold,
+                               const float *default_row, hps_fetch_fn fetch, void *user,
+                               hps_lookup_t **out_lookup) {
+    if (!out_lookup) return lfail(HPS_ERR_INVALID_ARG, "out_lookup is NULL");
+    *out_lookup = nullptr;
+    uint32_t dim = 0;
+    if (hps_cache_info(cache, nullptr, nullptr, &dim) != HPS_OK) return lfail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    if (!fetch || !default_row) return lfail(HPS_ERR_INVALID_ARG, "fetch and default_row are required");
+    if (max_batch == 0 || max_batch >= (1ull << 32)) return lfail(HPS_ERR_INVALID_ARG, "max_batch must be in [1, 2^32)");
+    hps_lookup_session *L = new (std::nothrow) hps_lookup_session();
+    if (!L) return lfail(HPS_ERR_OOM, "host allocation failed");
+    L->cache = cache; L->max_batch = max_batch; L->dim = dim; L->threshold = hit_threshold;
+    L->fetch = fetch; L->user = user;
+    L->d_miss_idx = L->d_n_miss = L->d_inv = nullptr; L->d_miss_keys = L->d_ukeys = nullptr;
+    L->d_rows = L->d_default = nullptr; L->h_n_miss = L->h_inv = nullptr; L->h_keys = L->h_ukeys = nullptr;
+    L->h_rows = nullptr; L->side = nullptr; L->bg_d_ukeys = nullptr; L->bg_d_rows = L->bg_h_rows = nullptr;
+    L->bg_h_ukeys = nullptr;
+    const size_t nb = max_batch, rowb = (size_t)dim * sizeof(float);
+    hipError_t e = hipGetDevice(&L->device);
+    auto dev = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
+    auto pin = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipHostMalloc(p, bytes, hipHostMallocDefault); };
+    dev((void **)&L->d_miss_idx, nb * 4); dev((void **)&L->d_n_miss, 4); dev((void **)&L->d_inv, nb * 4);
+    dev((void **)&L->d_miss_keys, nb * 8); dev((void **)&L->d_ukeys, nb * 8); dev((void **)&L->d_rows, nb * rowb);
+    dev((void **)&L->d_default, rowb); dev((void **)&L->bg_d_ukeys, nb * 8); dev((void **)&L->bg_d_rows, nb * rowb);
+    pin((void **)&L->h_n_miss, 4); pin((void **)&L->h_inv, nb * 4); pin((void **)&L->h_keys, nb * 8);
+    pin((void **)&L->h_ukeys, nb * 8); pin((void **)&L->h_rows, nb * rowb); pin((void **)&L->bg_h_rows, nb * rowb);
+    pin((void **)&L->bg_h_ukeys, nb * 8);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipMemcpy(L->d_default, default_row, rowb, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        const std::string msg = std::string("hps_lookup_create: ") + hipGetErrorString(e);
+        const hps_status_t code = e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE;
+        (void)hipGetLastError();
+        free_all(L);
+        delete L;
+        return lfail(code, msg);
+    }
+    L->worker = std::thread(worker_main, L);
+    *out_lookup = L;
+    return HPS_OK;
+}
+
+hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *out, float *hit_rate,
+                        int *was_synchronous, void *stream) {
+    if (!L) return lfail(HPS_ERR_INVALID_ARG, "lookup is NULL");
+    if (n > L->max_batch) return lfail(HPS_ERR_INVALID_ARG, "n exceeds max_batch");
+    {
+        std::lock_guard<std::mutex> lk(L->mu);
+        if (!L->worker_error.empty()) {
+            const std::string msg = L->worker_error;
+            L->worker_error.clear();
+            return lfail(HPS_ERR_DEVICE, msg);
+        }
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hit_rate) *hit_rate = 1.0f;
+    if (was_synchronous) *was_synchronous = 0;
+    if (n == 0) return HPS_OK;
+    // EmbCacheLookup(Q): hits land in out, misses in the workspace
+    if (hps_cache_query(L->cache, keys, n, out, L->d_miss_idx, L->d_miss_keys, L->d_n_miss, st) != HPS_OK)
+        return lfail(HPS_ERR_INVALID_ARG, std::string("query: ") + hps_last_error());
+    LK_TRY(hipMemcpyAsync(L->h_n_miss, L->d_n_miss, 4, hipMemcpyDeviceToHost, st));
+    LK_TRY(hipStreamSynchronize(st));
+    const uint32_t m = *L->h_n_miss;
+    const float rate = 1.0f - (float)m / (float)n;
+    if (hit_rate) *hit_rate = rate;
+    if (m == 0) return HPS_OK;
+
+    if (rate < L->threshold) {
+        // synchronous insertion: ParServerLookup(missing keys), EmbCacheInsert, E_Q <- fetched vectors
+        if (was_synchronous) *was_synchronous = 1;
+        LK_TRY(hipMemcpyAsync(L->h_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
+        LK_TRY(hipStreamSynchronize(st));
+        const uint32_t u = dedup_host(L->h_keys, m, L->h_ukeys, L->h_inv);
+        L->fetch(L->user, L->h_ukeys, u, L->h_rows);
+        LK_TRY(hipMemcpyAsync(L->d_ukeys, L->h_ukeys, (size_t)u * 8, hipMemcpyHostToDevice, st));
+        LK_TRY(hipMemcpyAsync(L->d_rows, L->h_rows, (size_t)u * L->dim * sizeof(float), hipMemcpyHostToDevice, st));
+        LK_TRY(hipMemcpyAsync(L->d_inv, L->h_inv, (size_t)m * 4, hipMemcpyHostToDevice, st));
+        launch_place(out, L->d_miss_idx, L->d_inv, L->d_rows, m, L->dim, st);
+        LK_TRY(hipGetLastError());
+        if (hps_cache_insert(L->cache, L->d_ukeys, L->d_rows, u, st) != HPS_OK)
+            return lfail(HPS_ERR_DEVICE, std::string("insert: ") + hps_last_error());
+        // the workspace is reused by the next call: make sure this one is done with it
+        LK_TRY(hipStreamSynchronize(st));
+        return HPS_OK;
+    }
+
+    // asynchronous insertion: default vectors now, the real rows reach the cache later
+    launch_place(out, L->d_miss_idx, nullptr, L->d_default, m, L->dim, st);
+    LK_TRY(hipGetLastError());
+    Task t;
+    t.m = m;
+    {
+        std::lock_guard<std::mutex> lk(L->mu);
+        if (!L->free_key_bufs.empty()) {
+            t.h_keys = L->free_key_bufs.back();
+            L->free_key_bufs.pop_back();
+        } else {
+            t.h_keys = nullptr;
+        }
+    }
+    if (!t.h_keys) LK_TRY(hipHostMalloc((void **)&t.h_keys, L->max_batch * 8, hipHostMallocDefault));
+    LK_TRY(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
+    LK_TRY(hipMemcpyAsync(t.h_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
+    LK_TRY(hipEventRecord(t.ready, st));
+    // the workspace's miss list is read by that copy; wait for it before the next call reuses it
+    LK_TRY(hipStreamSynchronize(st));
+    {
+        std::lock_guard<std::mutex> lk(L->mu);
+        L->queue.push_back(t);
+    }
+    L->cv.notify_one();
+    return HPS_OK;
+}
+
+hps_status_t hps_lookup_drain(hps_lookup_t *L) {
+    if (!L) return lfail(HPS_ERR_INVALID_ARG, "lookup is NULL");
+    std::unique_lock<std::mutex> lk(L->mu);
+    L->cv_idle.wait(lk, [&] { return L->queue.empty() && !L->busy; });
+    if (!L->worker_error.empty()) {
+        const std::string msg = L->worker_error;
+        L->worker_error.clear();
+        return lfail(HPS_ERR_DEVICE, msg);
+    }
+    return HPS_OK;
+}
+
+hps_status_t hps_lookup_destroy(hps_lookup_t *L) {
+    if (!L) return lfail(HPS_ERR_INVALID_ARG, "lookup is NULL");
+    (void)hps_lookup_drain(L);
+    {
+        std::lock_guard<std::mutex> lk(L->mu);
+        L->stop = true;
+    }
+    L->cv.notify_all();
+    if (L->worker.joinable()) L->worker.join();
+    free_all(L);
+    delete L;
+    return HPS_OK;
+}
+
+const char *hps_lookup_last_error(void) { return g_lookup_err.c_str(); }
+
+}  // extern "C"

@@ -7,13 +7,17 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "hps_cache.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))
+                 if f.endswith(".h"))
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hps_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = open(header).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(hps_[a-z_]+)\s*\(", text))
+    return sorted(names - {"hps_fetch_fn"})
 
 
 @pytest.fixture(scope="module")
@@ -53,6 +57,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.hps_cache_query_multi(None, 0, None, 0, None, None, None, None, None) == -1
     assert lib.hps_backing_fetch(None, 5, None, 6, 0, None, None, None, None) == -1
     assert lib.hps_backing_fetch(None, 5, None, 8, 0, None, None, None, None) == -1   # keys NULL
+    assert lib.hps_lookup(None, None, 0, None, None, None, None) == -1
+    assert lib.hps_lookup_drain(None) == -1 and lib.hps_lookup_destroy(None) == -1
+    assert len(lib.hps_lookup_last_error()) > 0
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):

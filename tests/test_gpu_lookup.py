@@ -1,0 +1,109 @@
+"""Algorithm 1 (cache lookup with hit-rate-controlled synchronous or asynchronous insertion)
+through hps_lookup against the same procedure written out over the oracle cache.
+
+The lower tiers are a Python callback that returns the backing generator's rows.  After every
+asynchronous lookup the test drains the background queue, which makes the cache state after each
+step unique; rows of `out`, hit rate, chosen mode and the canonical cache state are compared."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import OracleCache
+from paper_2210_08804_amd import binding as B
+from paper_2210_08804_amd import inputs
+from harness import DeviceCache, assert_same_state, check_state_invariants, insert_is_order_independent
+
+pytestmark = pytest.mark.gpu
+
+
+def make_fetch(d, log):
+    def fetch(user, keys_p, n, rows_p):
+        keys = np.ctypeslib.as_array(keys_p, shape=(n,))
+        assert len(np.unique(keys)) == n                      # the lower tiers see each key once
+        log.append(int(n))
+        np.ctypeslib.as_array(rows_p, shape=(n, d))[...] = inputs.backing_rows(keys, d, 0)
+    return B.FETCH_FN(fetch)
+
+
+def unique_in_order(a):
+    _, first = np.unique(a, return_index=True)
+    return a[np.sort(first)]
+
+
+def reference_step(oc, keys, d, threshold, default_row):
+    """Alg. 1 over the oracle.  Returns (out, hit_rate, synchronous, keys to insert after the call)."""
+    n = len(keys)
+    out = np.zeros((n, d), dtype=np.uint32)
+    _, mi, mk = oc.query(keys, out)
+    rate = np.float32(1.0) - np.float32(len(mi)) / np.float32(n)
+    if len(mi) == 0:
+        return out, rate, False, None
+    uk = unique_in_order(mk)
+    if rate < np.float32(threshold):
+        out[mi] = inputs.backing_rows(mk, d, 0).view(np.uint32)
+        return out, rate, True, uk
+    out[mi] = default_row.view(np.uint32)
+    return out, rate, False, uk
+
+
+@pytest.mark.parametrize("threshold", [0.0, 0.8, 2.0])
+def test_lookup_follows_algorithm_1(threshold):
+    S, W, d, n = 1 << 10, 8, 32, 6000
+    default_row = np.linspace(-1, 1, d).astype(np.float32)
+    log = []
+    fetch = make_fetch(d, log)
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        oc = OracleCache(S * W, W, d)
+        lk = B.hps_lookup_create(gc.h, n, threshold, default_row, fetch)
+        try:
+            modes = []
+            for step in range(14):
+                keys = inputs.zipf_keys(n if step % 3 else n // 2, 12000, 1.1, step + 1)
+                out = torch.zeros(len(keys), d, dtype=torch.float32, device="cuda")
+                rate, sync = B.hps_lookup(lk, torch.from_numpy(keys).cuda(), len(keys), out)
+                B.hps_lookup_drain(lk)
+                torch.cuda.synchronize()
+                exp_out, exp_rate, exp_sync, to_insert = reference_step(oc, keys, d, threshold, default_row)
+                assert np.float32(rate) == exp_rate and sync == exp_sync
+                assert (out.cpu().numpy().view(np.uint32) == exp_out).all()
+                modes.append(sync)
+                if to_insert is not None:
+                    exact = insert_is_order_independent(oc, to_insert)
+                    oc.insert(to_insert, inputs.backing_rows(to_insert, d, 0))
+                    state = gc.export()
+                    if exact:
+                        assert_same_state(state, oc)
+                    else:
+                        check_state_invariants(*state, oc.set_of)
+                    oc.load_state(*state)
+            if threshold == 0.0:
+                assert not any(modes)
+            elif threshold == 2.0:
+                assert all(modes)
+            else:
+                assert modes[0] and not modes[-1]             # warm-up synchronous, then asynchronous (Sec. 4.3)
+            assert len(log) >= 10
+        finally:
+            B.hps_lookup_destroy(lk)
+
+
+def test_lookup_argument_errors_and_empty_batch():
+    d = 16
+    fetch = make_fetch(d, [])
+    with DeviceCache(64, 8, d) as gc:
+        with pytest.raises(B.HpsError):
+            B.hps_lookup_create(None, 10, 0.5, np.zeros(d, np.float32), fetch)
+        with pytest.raises(B.HpsError):
+            B.hps_lookup_create(gc.h, 0, 0.5, np.zeros(d, np.float32), fetch)
+        lk = B.hps_lookup_create(gc.h, 100, 0.5, np.zeros(d, np.float32), fetch)
+        try:
+            keys = torch.zeros(200, dtype=torch.int64, device="cuda")
+            out = torch.zeros(200, d, dtype=torch.float32, device="cuda")
+            with pytest.raises(B.HpsError):
+                B.hps_lookup(lk, keys, 200, out)              # beyond max_batch
+            rate, sync = B.hps_lookup(lk, keys, 0, out)
+            assert rate == 1.0 and not sync
+        finally:
+            B.hps_lookup_destroy(lk)
