@@ -16,11 +16,6 @@ RESERVED_KEY = -(1 << 63) + 1
 SENTINEL = 0x7FC0DEAD          # bit pattern pre-filled into `out` (a NaN payload): must survive on miss rows
 
 
-def dev(a, dtype=None):
-    t = torch.from_numpy(np.ascontiguousarray(a))
-    if dtype is not None:
-        t = t.view(dtype) if t.element_size() == torch.empty((), dtype=dtype).element_size() else t.to(dtype)
-    return t.cuda()
 
 
 CONCURRENT_WRITERS = True      # which query variant new DeviceCache objects use (tests flip it)
