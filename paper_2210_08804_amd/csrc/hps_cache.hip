@@ -339,6 +339,7 @@ struct QueryArgs {
     uint32_t      *n_miss;
     uint64_t      *slot;        // per-call counter word: low 32 bits = misses so far, high 32 = tiles done
     uint32_t       B;           // keys per table
+    uint32_t       kpw;         // keys per worker wave (<= 64): lanes kpw..63 of a worker wave stay idle
     uint32_t       tiles_per_table;
     uint32_t       n_tiles;     // T * tiles_per_table (>= 1 even when B == 0)
     RowGeom        g;
@@ -363,7 +364,6 @@ struct QueryArgs {
 // absent from its slot), so only hits are validated.
 template <int W, int KPW, int U, int WPB, bool kCoherent>
 __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArgs a) {
-    constexpr int kTile = KPW * WPB;
     __shared__ uint64_t s_src[WPB][KPW];
     __shared__ uint32_t s_dst[WPB][KPW];
     __shared__ int64_t  s_mkey[WPB][KPW];
@@ -382,8 +382,8 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
         const uint32_t lt = tile - t * a.tiles_per_table;
         if (wave < WPB) {
             const Table   &tb   = a.tab[t];
-            const uint32_t b    = lt * kTile + wave * KPW + lane;
-            const bool     live = lane < KPW && b < a.B;
+            const uint32_t b    = (lt * WPB + wave) * a.kpw + lane;
+            const bool     live = lane < (int)a.kpw && b < a.B;
             const uint32_t pos  = t * a.B + b;         // position in keys/out (< 2^32 checked on host)
 
             const int64_t key  = live ? a.keys[pos] : kEmpty;
@@ -524,12 +524,12 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
     for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
         const uint32_t t  = tile / a.tiles_per_table;
         const uint32_t lt = tile - t * a.tiles_per_table;
-        const uint32_t pos0 = t * a.B + lt * kTile;            // position of this tile's first key
+        const uint32_t pos0 = t * a.B + lt * WPB * a.kpw;      // position of this tile's first key
         if (wave < WPB) {
             const Table   &tb   = a.tab[t];
-            const uint32_t tid  = (uint32_t)threadIdx.x;       // worker threads come first
-            const uint32_t b    = lt * kTile + tid;
-            const bool     live = b < a.B;
+            const uint32_t tid  = (uint32_t)wave * a.kpw + (uint32_t)lane;   // index in the tile (idle lanes alias, unused)
+            const uint32_t b    = lt * WPB * a.kpw + tid;
+            const bool     live = lane < (int)a.kpw && b < a.B;
             const uint32_t pos  = pos0 + tid;
             const int64_t  key  = live ? a.keys[pos] : kEmpty;
             const bool     want = live && !is_reserved(key);
@@ -537,8 +537,8 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
             const uint32_t hs   = (uint32_t)(h >> 32);
             const uint32_t set  = want ? (tb.smask ? (hs & tb.smask) : (hs % tb.S)) : 0u;
 
-            for (uint32_t i = tid; i < (uint32_t)kHash; i += kTile) h_key[i] = (unsigned long long)kEmpty;
-            head[tid] = kNil;
+            for (uint32_t i = threadIdx.x; i < (uint32_t)kHash; i += kTile) h_key[i] = (unsigned long long)kEmpty;
+            head[threadIdx.x] = kNil;
             __syncthreads();                                    // #1 table cleared
 
             bool is_rep = false;
@@ -1001,6 +1001,7 @@ struct hps_cache {
     uint32_t *T;                          // access stamps (LRU policy), else nullptr
     std::atomic<uint32_t> g;              // global iteration count: one step per query call (LRU policy)
     uint32_t *flags;                      // device word of HPS_FLAG_* bits
+    int      n_cus;                       // compute units of the device
 };
 
 namespace {
@@ -1175,6 +1176,9 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->query_dedup.store(0);
 
     hipError_t e = hipGetDevice(&c->device);
+    c->n_cus = 256;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device);
+    if (e == hipSuccess && c->n_cus <= 0) c->n_cus = 256;
     if (e == hipSuccess) e = hipMalloc(&c->K, capacity * sizeof(int64_t));
     if (e == hipSuccess) e = hipMalloc(&c->V, capacity * (size_t)dim * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&c->ctr, c->S * sizeof(uint32_t));
@@ -1297,7 +1301,21 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     a.slot = next_slot(caches[0]);
     a.B = (uint32_t)batch;
     const QueryShape shape = query_shape(total);
-    const uint32_t tile = (uint32_t)(shape.kpw * shape.wpb);
+    // Keys per worker wave: at most 64, trimmed so that the work-groups come out as a whole number
+    // of rounds over the CUs (106,496 keys in tiles of 8 x 52 are exactly 256 work-groups; tiles of
+    // 8 x 64 would be 208, leaving 48 CUs idle).
+    uint32_t kpw = (uint32_t)shape.kpw;
+    {
+        const uint64_t cus = (uint64_t)caches[0]->n_cus;
+        const uint64_t full = (uint64_t)shape.wpb * shape.kpw * cus;       // keys per round at 64 keys per wave
+        const uint64_t rounds = (total + full - 1) / full;
+        if (rounds > 0 && rounds <= 8) {
+            const uint64_t k = (total + shape.wpb * cus * rounds - 1) / (shape.wpb * cus * rounds);
+            if (k >= 32 && k <= (uint64_t)shape.kpw) kpw = (uint32_t)k;
+        }
+    }
+    a.kpw = kpw;
+    const uint32_t tile = kpw * (uint32_t)shape.wpb;
     a.tiles_per_table = (uint32_t)((batch + tile - 1) / tile);
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
