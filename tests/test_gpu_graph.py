@@ -1,0 +1,72 @@
+"""Query, insert and update captured into a HIP graph: the library records no memset nodes (the
+miss counter resets itself), so replays must keep giving the eager results.  Each replay is
+checked, with eager work and synchronisations in between."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import OracleCache
+from paper_2210_08804_amd import binding as B
+from paper_2210_08804_amd import inputs
+from harness import DeviceCache, SENTINEL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("checked", [False, True])
+def test_graph_replays_match_eager_results(checked):
+    S, W, d, n = 1 << 10, 8, 64, 5000
+    with DeviceCache(S * W, W, d, concurrent_writers=checked) as gc:
+        oc = OracleCache(S * W, W, d)
+        ids = np.arange(4000, dtype=np.int64)
+        for ck in np.array_split(ids, 8):
+            gc.insert(ck, inputs.backing_rows(ck, d))
+        oc.load_state(*gc.export())
+        batches = [inputs.zipf_keys(n, 9000, 1.05, 50 + b) for b in range(3)]
+        dk = [torch.from_numpy(k).cuda() for k in batches]
+        outs = [torch.empty(n, d, dtype=torch.float32, device="cuda") for _ in batches]
+        mi = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in batches]
+        mk = [torch.empty(n, dtype=torch.int64, device="cuda") for _ in batches]
+        nm = torch.zeros(3, dtype=torch.int32, device="cuda")
+        upd_keys = torch.from_numpy(ids[:512].copy()).cuda()
+        upd_rows = torch.empty(512, d, dtype=torch.float32, device="cuda")
+
+        g = torch.cuda.CUDAGraph()
+        cs = torch.cuda.Stream()
+        cs.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cs):
+            g.capture_begin()
+            for b in range(3):
+                B.hps_cache_query(gc.h, dk[b], n, outs[b], mi[b], mk[b], nm[b:b + 1], cs)
+            B.hps_cache_update(gc.h, upd_keys, upd_rows, 512, cs)       # takes effect after the three queries
+            g.capture_end()
+        torch.cuda.synchronize()
+
+        for replay in range(4):
+            # eager work between replays: new rows for the update, scribble over the outputs
+            version = replay + 1
+            B.hps_backing_fetch(upd_keys, 512, d, version=version, rows=upd_rows)
+            for o in outs:
+                o.view(torch.int32).fill_(SENTINEL)
+            nm.fill_(-7)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for b in range(3):
+                exp = np.full((n, d), SENTINEL, dtype=np.uint32)
+                _, omi, omk = oc.query(batches[b], exp)
+                m = int(nm[b].item())
+                order = np.argsort(mi[b][:m].cpu().numpy().view(np.uint32))
+                assert m == len(omi), f"replay {replay}, batch {b}"
+                assert (mi[b][:m].cpu().numpy().view(np.uint32)[order] == omi).all()
+                assert (mk[b][:m].cpu().numpy()[order] == omk).all()
+                got = outs[b].view(torch.int32).cpu().numpy().view(np.uint32)
+                bad = np.nonzero((got != exp).any(axis=1))[0]
+                assert bad.size == 0, (f"replay {replay}, batch {b}: {bad.size} rows differ, first at position {bad[:5]}, "
+                                       f"keys {batches[b][bad[:5]]}, got {got[bad[0], :3]} expected {exp[bad[0], :3]}")
+            oc.update(ids[:512], inputs.backing_rows(ids[:512], d, version))
+            # an eager query in between sees the update of the replay
+            got, gmi, _ = gc.query(ids[:512])
+            exp = np.full((512, d), SENTINEL, dtype=np.uint32)
+            _, omi, _ = oc.query(ids[:512], exp)
+            assert (gmi == omi).all() and (got == exp).all() and len(omi) < 100
