@@ -1062,7 +1062,7 @@ template <int W, int KPW, int U, int WPB>
 void launch_query_shape(const QueryArgs &a, bool coherent, bool dedup, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
-    if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 8, WPB, true>), dim3(grid), block, 0, st, a);
+    if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true>), dim3(grid), block, 0, st, a);
     else if (dedup && KPW == kWave)
         hipLaunchKernelGGL((query_dedup_kernel<W, U, WPB>), dim3(grid), block, 0, st, a);
     else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false>), dim3(grid), block, 0, st, a);
