@@ -19,8 +19,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <unordered_map>
 
 #include "hps_cache.h"
 
@@ -30,7 +32,7 @@ constexpr int64_t  kEmpty      = INT64_MIN;
 constexpr int      kBlock      = 256;          // threads per work-group: 4 waves of 64
 constexpr int      kWave       = 64;
 constexpr int      kWavesPerWg = kBlock / kWave;
-constexpr uint32_t kRing       = 1024;         // per-call counter slots (see QueryArgs::slot)
+constexpr uint32_t kRing       = 1024;         // counter words, one per stream seen (see counter_word)
 constexpr uint64_t kMagic      = 0x4850534341434845ull;
 // Every loop that waits for another kernel's writer to let go of a set gives up after this many
 // rounds (a held set is released within microseconds; this many rounds take about a second) and
@@ -994,7 +996,8 @@ struct hps_cache {
     uint32_t *ctr;
     uint32_t *seq;
     uint64_t *ring;                       // kRing counter words, all zero between calls
-    std::atomic<uint32_t> calls;
+    std::mutex word_mu;
+    std::unordered_map<void *, uint32_t> word_of_stream;
     std::atomic<int> concurrent_writers;
     std::atomic<int> query_dedup;
     int      policy;                      // HPS_POLICY_*
@@ -1031,8 +1034,16 @@ Table table_of(const hps_cache *c) {
     return t;
 }
 
-uint64_t *next_slot(hps_cache *c) {
-    return c->ring + (c->calls.fetch_add(1, std::memory_order_relaxed) % kRing);
+// Counter word of query/dump calls on `stream`.  Calls on one stream run one after the other and
+// each leaves its word at zero, so they can share one; calls on different streams may overlap and
+// get different words (the first kRing streams seen; beyond that words are shared modulo kRing).
+// A kernel captured into a graph keeps the word of the stream it was captured on.
+uint64_t *counter_word(hps_cache *c, void *stream) {
+    std::lock_guard<std::mutex> lk(c->word_mu);
+    auto it = c->word_of_stream.find(stream);
+    if (it == c->word_of_stream.end())
+        it = c->word_of_stream.emplace(stream, (uint32_t)(c->word_of_stream.size() % kRing)).first;
+    return c->ring + it->second;
 }
 
 // Launch shape of the query kernel: KPW keys per worker wave, U wave loads in flight, WPB worker
@@ -1171,7 +1182,6 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr;
     c->policy = policy;
     c->g.store(0);
-    c->calls.store(0);
     c->concurrent_writers.store(1);
     c->query_dedup.store(0);
 
@@ -1298,7 +1308,7 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     a.miss_idx = miss_idx;
     a.miss_keys = miss_keys;
     a.n_miss = n_miss;
-    a.slot = next_slot(caches[0]);
+    a.slot = counter_word(caches[0], stream);
     a.B = (uint32_t)batch;
     const QueryShape shape = query_shape(total);
     // Keys per worker wave: at most 64, trimmed so that the work-groups come out as a whole number
@@ -1411,7 +1421,7 @@ hps_status_t hps_cache_dump(hps_cache_t *c, size_t first_slot, size_t n_slots, i
     if (n_tiles == 0) n_tiles = 1;
     const uint32_t grid = n_tiles < (1u << 20) ? n_tiles : (1u << 20);
     hipLaunchKernelGGL((dump_kernel<kDumpKpt>), dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), c->K,
-                       (uint64_t)first_slot, (uint64_t)n_slots, c->W, keys_out, n_out, next_slot(c), n_tiles);
+                       (uint64_t)first_slot, (uint64_t)n_slots, c->W, keys_out, n_out, counter_word(c, stream), n_tiles);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
