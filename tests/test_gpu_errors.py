@@ -92,3 +92,16 @@ def test_a_set_that_is_never_released_cannot_hang_a_kernel():
         assert (out[resident & ~in_stuck] == new_rows.view(np.uint32)[resident & ~in_stuck]).all()
         assert (out[resident & in_stuck] == rows.view(np.uint32)[resident & in_stuck]).all()   # those updates were skipped
         assert B.hps_cache_flags(gc.h) == 0
+
+
+def test_create_reports_out_of_memory_and_recovers():
+    lib = B.load_library()
+    h = C.c_void_p()
+    # 2^33 slots of 512 bytes = 4 TiB of rows: more than the device has
+    assert lib.hps_cache_create(1 << 33, 8, 128, C.byref(h)) == B.HPS_ERR_OOM
+    assert h.value is None and "hps_cache_create" in B.hps_last_error()
+    with DeviceCache(1 << 12, 8, 128) as gc:                 # the device is still usable afterwards
+        keys = np.arange(100, dtype=np.int64)
+        gc.insert(keys, inputs.backing_rows(keys, 128))
+        out, mi, _ = gc.query(keys)
+        assert mi.size == 0 and (out == inputs.backing_rows(keys, 128).view(np.uint32)).all()
