@@ -131,7 +131,7 @@ def refresh(a, np, torch, B):
                    "paper_table3_A100": {"update_ms": paper[0], "dump_ms": paper[1]} if paper else None},
         "roofline": {"bound": "hbm", "achieved": round(alg / (upd_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(alg / (upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "write_kernel<8,false>", "algorithmic_bytes_per_launch": alg,
+                     "kernel": "update_kernel<8>", "algorithmic_bytes_per_launch": alg,
                      "us_per_launch": round(upd_ms * 1e3, 1)},
     }
     torch.cuda.synchronize()

@@ -267,8 +267,12 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
     }
 }
 
-// Writer side: copy `cnt` rows listed in LDS from the caller's batch into the cache with
+// Writer side: copy `cnt` (> 0) rows listed in LDS from the caller's batch into the cache with
 // shared_st64 (8 bytes per lane), so that overlapping readers observe them without cache flushes.
+// Two register buffers alternate: the loads of the next U wave loads are issued before the
+// stores of the current ones, so a write-through store's long acknowledgement never sits between
+// a wave and its next loads.  Lanes past the list repeat entry 0 (same bytes to the same place),
+// and the loads issued past the last group re-read entry 0 and are dropped.
 template <int U>
 __device__ __forceinline__ void copy_rows_shared(const RowGeom g, const float *__restrict__ src,
                                                  float *dst, const uint32_t *srcRow,
@@ -277,21 +281,33 @@ __device__ __forceinline__ void copy_rows_shared(const RowGeom g, const float *_
     const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;
     const uint32_t sub = lane >> g.lpr8Shift;
     const uint32_t cl  = lane & (g.LPR8 - 1);
+    const uint32_t step = rpi * U;
     for (uint32_t pass = 0; pass < g.passes8; ++pass) {
         uint32_t chunk = cl + pass * g.LPR8;
         chunk = chunk < g.C8 ? chunk : 0u;
-        for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
-            uint64_t buf[U];
-            uint32_t ent[U];
+        uint64_t bufA[U], bufB[U];
+        uint32_t entA[U], entB[U];
+        auto load = [&](uint32_t e0, uint64_t (&buf)[U], uint32_t (&ent)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint32_t e = e0 + u * rpi + sub;
                 ent[u] = e < cnt ? e : 0u;
                 buf[u] = *(reinterpret_cast<const uint64_t *>(src + (uint64_t)srcRow[ent[u]] * g.d) + chunk);
             }
+        };
+        auto store = [&](const uint64_t (&buf)[U], const uint32_t (&ent)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 shared_st64(reinterpret_cast<uint64_t *>(dst + dstRow[ent[u]] * g.d) + chunk, buf[u]);
+        };
+        load(0, bufA, entA);
+        for (uint32_t e0 = 0;; e0 += 2 * step) {
+            load(e0 + step, bufB, entB);
+            store(bufA, entA);
+            if (e0 + step >= cnt) break;
+            load(e0 + 2 * step, bufA, entA);
+            store(bufB, entB);
+            if (e0 + 2 * step >= cnt) break;
         }
     }
 }
@@ -654,16 +670,18 @@ struct WriteArgs {
     RowGeom         g;
 };
 
-// Replace (Alg. 3) and Update (Alg. 4).  One key per lane.  A lane that has to write takes its
-// set's sequence word from even to odd with a compare-and-swap (the paper's slabset lock,
-// Sec. 4.1), after an optimistic search of the set: the swap succeeds only if no other writer
-// finished in between, so the search result still holds under the lock.  Lanes never wait while
-// the wave holds a lock: each round every pending lane tries once, the winners' rows are copied
-// by the whole wave, the locks are released, and the losers try again.
-//   insert: key found -> ignored; else way = ctr mod W, ctr += 1, key and row written
-//   update: key not found -> ignored; else row overwritten
-template <int W, bool kInsert>
-__global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
+// Replace (Alg. 3).  The first KPW lanes of a wave own one key each; all 64 lanes copy rows.  A
+// pending lane takes its set's sequence word (the paper's slabset lock, Sec. 4.1) with one
+// fetch-or of bit 0: it owns the set if the bit was clear.  The owners' sets are then searched with the wave-wide probe and their
+// counters read in the same round trip, new keys get their slot (key, counter, stamp) and row,
+// and every owner lets go again: word + 2 if it changed the set, the old word if the key was
+// already there.  Lanes that did not get their set search it without owning it before every
+// further attempt.  No lane ever waits while the wave owns a set: each round every pending lane
+// tries once, the owners' rows are copied by the whole wave, the sets are released, and the
+// others try again.  Small batches use KPW = 16 so that four times as many waves share the row
+// copies.
+template <int W, int KPW>
+__global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
     __shared__ uint64_t s_dst[kWavesPerWg][kWave];
     __shared__ uint32_t s_srcrow[kWavesPerWg][kWave];
 
@@ -676,14 +694,15 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
         const uint32_t nd = *a.n_dev;
         n = nd < n ? nd : n;
     }
-    const uint32_t n_tiles = (n + kWave - 1) / kWave;
+    const uint32_t n_tiles = (n + KPW - 1) / KPW;
     const uint32_t wave_global = blockIdx.x * kWavesPerWg + wave;
     const uint32_t n_waves = gridDim.x * kWavesPerWg;
 
     for (uint32_t tile = wave_global; tile < n_tiles; tile += n_waves) {
-        const uint32_t i = tile * kWave + lane;
-        const int64_t key = i < n ? a.keys[i] : kEmpty;
-        bool pending = i < n && !is_reserved(key);
+        const uint32_t i = tile * KPW + lane;
+        const bool mine = lane < KPW && i < n;
+        const int64_t key = mine ? a.keys[i] : kEmpty;
+        bool pending = mine && !is_reserved(key);
         const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
 
         uint32_t rounds = 0;
@@ -693,67 +712,63 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
                                                    __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
-            bool won = false;
-            uint32_t v = 0;
-            int way = -1;
-            int empty_way = -1;
-            if (pending) {
-                v = ld_agent(tb.seq + set);
-                if (!(v & 1u)) {
+            if (rounds > 1) {
+                // A lane that lost its first attempt looks before it tries again: a key given many
+                // times (a miss list carries every occurrence) is found by all but the first
+                // without taking the word, instead of each occurrence owning the set in turn.
+                const int seen = probe_wave<W, KPW, true>(tb.K, key, set, pending);
+                if (pending && seen >= 0) {
+                    if (tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)seen, tb.g);     // Alg. 3: refresh
+                    pending = false;
+                }
+            }
+            uint32_t old = 1u;
+            if (pending) old = __hip_atomic_fetch_or(tb.seq + set, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool own = pending && !(old & 1u);
+            if (!__ballot(own)) {
+                __builtin_amdgcn_s_sleep(8);
+                continue;
+            }
+            shared_acquire();                                        // the word is owned before the set is read
+            int way = probe_wave<W, KPW, true>(tb.K, key, set, own);
+            const uint32_t c = own ? ld_agent(tb.ctr + set) : 0u;
+            bool fresh = own && way < 0;
+            if (tb.T) {                                              // LRU policy (Alg. 3)
+                if (fresh) {
+                    int empty_way = -1;
+                    uint32_t best = 0;
+                    int oldest = 0;
 #pragma unroll
                     for (int w = W - 1; w >= 0; --w) {
                         const int64_t kw = ld_agent(tb.K + (uint64_t)set * W + w);
-                        if (kw == key) way = w;
-                        if (kw == kEmpty) empty_way = w;      // ends as the lowest empty way
+                        const uint32_t age = tb.g - ld_agent(tb.T + (uint64_t)set * W + w);
+                        if (kw == kEmpty) empty_way = w;             // ends as the lowest empty way
+                        if (w == W - 1 || age >= best) { best = age; oldest = w; }   // largest age, lowest way on ties
                     }
-                    const bool found = way >= 0;
-                    if (found == kInsert) {
-                        pending = false;                      // insert: already cached; update: absent
-                        if (kInsert && tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);   // Alg. 3: refresh
-                    } else {
-                        uint32_t expect = v;
-                        won = __hip_atomic_compare_exchange_strong(
-                            tb.seq + set, &expect, v + 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                            __HIP_MEMORY_SCOPE_AGENT);
-                    }
+                    way = empty_way >= 0 ? empty_way : oldest;
                 }
+                if (own) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);
+            } else if (fresh) {
+                way = (int)(c & (W - 1));                            // victim counter
             }
-            const uint64_t wonmask = __ballot(won);
-            if (wonmask) {
-                shared_acquire();
-                if (won) {
-                    if (kInsert) {
-                        const uint32_t c = ld_agent(tb.ctr + set);
-                        if (!tb.T) {
-                            way = (int)(c & (W - 1));                 // victim counter
-                        } else if (empty_way >= 0) {
-                            way = empty_way;                          // empty slots first
-                        } else {                                      // least recently used: largest age
-                            uint32_t best = 0;
-                            way = 0;
-#pragma unroll
-                            for (int w = 0; w < W; ++w) {
-                                const uint32_t age = tb.g - ld_agent(tb.T + (uint64_t)set * W + w);
-                                if (w == 0 || age > best) { best = age; way = w; }
-                            }
-                        }
-                        if (tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);
-                        st_agent(tb.ctr + set, c + 1u);
-                        st_agent(tb.K + (uint64_t)set * W + way, key);
-                    }
-                    const int r = rank_in(wonmask);
-                    s_dst[wave][r] = (uint64_t)set * W + (uint32_t)way;
-                    s_srcrow[wave][r] = i;
-                }
+            const uint64_t freshmask = __ballot(fresh);
+            if (fresh) {
+                st_agent(tb.ctr + set, c + 1u);
+                st_agent(tb.K + (uint64_t)set * W + (uint32_t)way, key);
+                const int r = rank_in(freshmask);
+                s_dst[wave][r] = (uint64_t)set * W + (uint32_t)way;
+                s_srcrow[wave][r] = i;
+            }
+            if (freshmask) {
                 wave_lds_fence();
                 copy_rows_shared<8>(g, a.vals, tb.V, &s_srcrow[wave][0], &s_dst[wave][0],
-                                    (uint32_t)__popcll(wonmask));
+                                    (uint32_t)__popcll(freshmask));
                 wave_lds_fence();
-                shared_release();                                    // rows and key land before the word moves on
-                if (won) {
-                    st_agent(tb.seq + set, v + 2u);
-                    pending = false;
-                }
+            }
+            shared_release();                                        // rows and keys land before the words move on
+            if (own) {
+                st_agent(tb.seq + set, fresh ? old + 2u : old);
+                pending = false;
             }
         }
     }
@@ -765,7 +780,8 @@ __global__ void __launch_bounds__(kBlock) write_kernel(const WriteArgs a) {
 // with the same set form a group; the group's first lane reads the word and, if any lane of the
 // group found its key, takes it once; all those lanes' rows are then written under that one hold.
 // Two lanes of a group that found the same slot (a key given twice) are thinned to one per round.
-// Lanes of different groups that meet on a set compete by compare-and-swap as in write_kernel.
+// Lanes of different groups that meet on a set compete by compare-and-swap on its word; no lane
+// waits while its wave owns a set.
 template <int W>
 __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
     __shared__ uint64_t s_dst[kWavesPerWg][kWave];
@@ -1116,14 +1132,17 @@ hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, 
     a.n_dev = n_dev;
     a.n = (uint32_t)n;
     a.g = make_geom(c->d);
-    const uint64_t tiles = (n + kWave - 1) / kWave;
+    // insert: 16 keys per wave while 64 would leave fewer than 8 waves per CU
+    const uint32_t kpw = (kInsert && n < (size_t)c->n_cus * 8 * kWave) ? 16u : (uint32_t)kWave;
+    const uint64_t tiles = (n + kpw - 1) / kpw;
     uint64_t blocks = (tiles + kWavesPerWg - 1) / kWavesPerWg;
     if (blocks > (1u << 16)) blocks = 1u << 16;
     const dim3 grid((uint32_t)blocks), block(kBlock);
     switch (c->W) {
 #define HPS_CASE(w)                                                                         \
     case w:                                                                                 \
-        if (kInsert) hipLaunchKernelGGL((write_kernel<w, true>), grid, block, 0, st, a);    \
+        if (kInsert && kpw == 16) hipLaunchKernelGGL((insert_kernel<w, 16>), grid, block, 0, st, a); \
+        else if (kInsert) hipLaunchKernelGGL((insert_kernel<w, 64>), grid, block, 0, st, a); \
         else hipLaunchKernelGGL((update_kernel<w>), grid, block, 0, st, a);                 \
         break;
         HPS_CASE(1) HPS_CASE(2) HPS_CASE(4) HPS_CASE(8) HPS_CASE(16) HPS_CASE(32) HPS_CASE(64)

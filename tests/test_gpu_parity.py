@@ -203,6 +203,30 @@ def test_duplicates_with_different_rows_store_one_intact():
         assert (out[0] == out[0, 0]).all() and 1000 <= out[0, 0] < 1500
 
 
+def test_key_given_very_many_times_does_not_starve_its_set():
+    """A miss list carries every occurrence of a missing key, so a hot key can come tens of
+    thousands of times in one insert batch.  Keys that share its set, each given once, must
+    still get in, and no wave may give up (the flag word is checked when the cache closes)."""
+    from oracle import set_of
+    S, W, d = 1 << 10, 8, 128
+    hot = 1
+    mates = [k for k in range(2, 200000) if set_of(k, S) == set_of(hot, S)][:W - 1]
+    assert len(mates) == W - 1
+    other = np.unique(inputs.uniform_keys(1500, 1 << 40, 21))
+    other = other[[set_of(int(k), S) != set_of(hot, S) for k in other]]
+    keys = np.concatenate([np.full(120000, hot, dtype=np.int64), np.array(mates, dtype=np.int64), other])
+    keys = keys[np.random.Generator(np.random.PCG64(8)).permutation(len(keys))]
+    with DeviceCache(S * W, W, d) as gc:
+        oc = OracleCache(S * W, W, d)
+        insert_both(gc, oc, keys, rows_u32(keys, d))
+        resident = set(np.array(oc.keys).reshape(-1).tolist())
+        assert hot in resident and set(mates) <= resident
+        compare_query(gc, oc, np.concatenate([keys[:4096], np.array(mates, dtype=np.int64)]))
+        # the same batch again: every key is cached now, nothing changes
+        insert_both(gc, oc, keys, rows_u32(keys, d, version=1))
+        compare_query(gc, oc, keys[:4096])
+
+
 def test_one_set_overflow_keeps_invariants():
     # all keys of the batch fall into one set of a 4-way cache: far more than W new keys
     S, W, d = 8, 4, 8
