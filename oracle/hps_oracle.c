@@ -17,6 +17,9 @@
  *   - Update, Sec. 4.2 and Alg. 4: a cached key gets its vector overwritten; any other key is
  *     ignored.
  *   - Dump, Sec. 4.2: the keys currently cached.
+ *   - Deduplication, Sec. 2.2: Q* = dedup(Q), the distinct keys of a query batch, with the map
+ *     from every position of Q to its key's place in Q* (what a caller needs to hand every
+ *     position its row after looking up Q* only).
  *
  * Readings where the paper is silent or differs from this build's contract:
  *   - Geometry: a set has W slots (W a power of two, 1..64); the paper's 32-slot slabs and
@@ -38,6 +41,9 @@
  *   - Duplicates in a batch are handled by plain index order: every missing position gets
  *     its own miss-list entry; the first occurrence of a new key inserts, later ones find it.
  *   - Rows are opaque 32-bit patterns (no floating-point arithmetic anywhere).
+ *   - dedup: the paper fixes no order of Q*; here it is the order of first occurrence (any
+ *     permutation of Q* with the matching map is an equally valid result).  All 2^64 key values
+ *     are ordinary to dedup, the two reserved ones included.
  *
  * Every batch is processed sequentially in index order.
  */
@@ -222,4 +228,28 @@ uint64_t hpso_dump(const hpso_t *c, int64_t *keys_out)
         if (c->K[i] != HPSO_EMPTY)
             keys_out[m++] = c->K[i];
     return m;
+}
+
+/*
+ * dedup (Sec. 2.2): unique_out receives the distinct keys in order of first occurrence,
+ * inverse_out[i] the place of keys[i] among them.  Returns |Q*|.  Written as the definition: every
+ * key is compared with the distinct keys found so far.
+ */
+uint64_t hpso_dedup(const int64_t *keys, uint64_t n, int64_t *unique_out, uint32_t *inverse_out)
+{
+    uint64_t u = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t j = 0;
+        while (j < u && unique_out[j] != keys[i]) ++j;
+        if (j == u) unique_out[u++] = keys[i];
+        inverse_out[i] = (uint32_t)j;
+    }
+    return u;
+}
+
+/* The step after looking up Q*: position i gets the row of its key, out[i] = rows[inverse[i]]. */
+void hpso_expand(const uint32_t *rows, const uint32_t *inverse, uint64_t n, uint32_t d, uint32_t *out)
+{
+    for (uint64_t i = 0; i < n; ++i)
+        memcpy(out + i * d, rows + (uint64_t)inverse[i] * d, sizeof(uint32_t) * d);
 }

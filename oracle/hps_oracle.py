@@ -52,6 +52,10 @@ def load_library(path=None):
     lib.hpso_update.argtypes = [vp, vp, vp, u64]
     lib.hpso_dump.restype = u64
     lib.hpso_dump.argtypes = [vp, vp]
+    lib.hpso_dedup.restype = u64
+    lib.hpso_dedup.argtypes = [vp, u64, vp, vp]
+    lib.hpso_expand.restype = None
+    lib.hpso_expand.argtypes = [vp, vp, u64, u32, vp]
     if path is None:
         _lib = lib
     return lib
@@ -174,3 +178,26 @@ class OracleCache:
 def set_of(key: int, num_sets: int, lib=None) -> int:
     """Set index of a key for a cache with `num_sets` sets (same rule as the C file, via its mix64)."""
     return (mix64(key, lib) >> 32) % num_sets
+
+
+def dedup(keys, lib=None):
+    """Q* = dedup(Q) (Sec. 2.2): (distinct keys in order of first occurrence, inverse map)."""
+    keys = _keys(keys)
+    n = keys.shape[0]
+    uniq = np.empty(max(n, 1), dtype=np.int64)
+    inv = np.empty(max(n, 1), dtype=np.uint32)
+    u = (lib or _load()).hpso_dedup(keys.ctypes.data, n, uniq.ctypes.data, inv.ctypes.data)
+    return uniq[:u].copy(), inv[:n].copy()
+
+
+def expand(rows, inverse, lib=None):
+    """out[i] = rows[inverse[i]] for rows given as [u, d] uint32/float32 bit patterns."""
+    rows = np.ascontiguousarray(rows)
+    if rows.dtype == np.float32:
+        rows = rows.view(np.uint32)
+    inverse = np.ascontiguousarray(inverse, dtype=np.uint32)
+    n, d = inverse.shape[0], rows.shape[1]
+    assert n == 0 or int(inverse.max()) < rows.shape[0]
+    out = np.empty((n, d), dtype=np.uint32)
+    (lib or _load()).hpso_expand(rows.ctypes.data, inverse.ctypes.data, n, d, out.ctypes.data)
+    return out

@@ -11,6 +11,7 @@ import pytest
 import oracle
 from oracle import hps_oracle
 
+import test_oracle_dedup as dedup_pins
 import test_oracle_lru as lru_pins
 import test_oracle_pins as pins
 
@@ -42,6 +43,10 @@ MUTANTS = [
     ("lru: youngest instead of oldest evicted", "(uint32_t)(c->g - c->T[s * c->W + x]) > (uint32_t)(c->g - c->T[s * c->W + w])", "(uint32_t)(c->g - c->T[s * c->W + x]) < (uint32_t)(c->g - c->T[s * c->W + w])"),
     ("lru: ties go to the highest way", "(uint32_t)(c->g - c->T[s * c->W + x]) > (uint32_t)(c->g - c->T[s * c->W + w])", "(uint32_t)(c->g - c->T[s * c->W + x]) >= (uint32_t)(c->g - c->T[s * c->W + w])"),
     ("lru: stamps compared without wrap-around", "(uint32_t)(c->g - c->T[s * c->W + x]) > (uint32_t)(c->g - c->T[s * c->W + w])", "c->T[s * c->W + x] < c->T[s * c->W + w]"),
+    ("dedup: only the previous distinct key is compared", "        uint64_t j = 0;\n        while (j < u && unique_out[j] != keys[i]) ++j;", "        uint64_t j = u ? u - 1 : 0;\n        while (j < u && unique_out[j] != keys[i]) ++j;"),
+    ("dedup: place counted from one", "        inverse_out[i] = (uint32_t)j;", "        inverse_out[i] = (uint32_t)j + 1;"),
+    ("dedup: a repeated key is listed again", "        if (j == u) unique_out[u++] = keys[i];", "        if (j == u || j == 0) unique_out[u++] = keys[i];"),
+    ("expand: position used instead of the map", "memcpy(out + i * d, rows + (uint64_t)inverse[i] * d, sizeof(uint32_t) * d);", "memcpy(out + i * d, rows + (i < 37 ? i : 0) * d, sizeof(uint32_t) * d);"),
     ("lru: new key not stamped", "            c->T[s * c->W + w] = c->g;\n        }\n        c->C[s] += 1;", "        }\n        c->C[s] += 1;"),
 ]
 
@@ -61,6 +66,8 @@ def battery(lib, monkeypatch):
         monkeypatch.setattr(mod, "OracleCache", cache)
     monkeypatch.setattr(pins, "mix64", functools.partial(hps_oracle.mix64, lib=lib))
     monkeypatch.setattr(oracle, "set_of", functools.partial(hps_oracle.set_of, lib=lib))
+    monkeypatch.setattr(oracle, "dedup", functools.partial(hps_oracle.dedup, lib=lib))
+    monkeypatch.setattr(oracle, "expand", functools.partial(hps_oracle.expand, lib=lib))
     checks = [
         ("published hash vectors", pins.test_mix64_published_vectors),
         ("hash vs big integers", pins.test_mix64_against_bigint_many_keys),
@@ -82,6 +89,11 @@ def battery(lib, monkeypatch):
         ("lru batched model 7x8", lambda: lru_pins.test_batched_calls_match_independent_model(7, 8)),
         ("lru touched keys survive", lru_pins.test_keys_touched_by_a_call_outlive_untouched_ones),
         ("policy 0 ignores stamps", lru_pins.test_policy0_is_unaffected_by_stamps),
+        ("dedup worked example", dedup_pins.test_worked_example),
+        ("dedup degenerate batches", dedup_pins.test_degenerate_batches),
+        ("dedup vs set/dict/numpy", lambda: dedup_pins.test_against_set_dict_and_numpy_unique(1, 1.05)),
+        ("dedup brute force", dedup_pins.test_brute_force_small_alphabets),
+        ("expand is a gather", dedup_pins.test_expand_is_a_row_gather),
     ]
     for name, fn in checks:
         try:
