@@ -6,7 +6,9 @@
  * background (asynchronous insertion).
  *
  * The lower storage tiers (Sec. 5) are the caller's: a fetch callback that receives the missing
- * keys in host memory and fills their rows in host memory.  Everything else runs on the device.
+ * keys in host memory and fills their rows in host memory.  Everything else runs on the device,
+ * including the deduplication of the missing keys (Sec. 2.2, hps_dedup.h): only distinct keys
+ * travel to the host.
  * One lookup object serves one stream of batches (it owns one workspace, the paper's `ws`); use
  * one object per concurrent inference worker, all on the same cache.
  */
@@ -23,7 +25,8 @@ typedef struct hps_lookup_session hps_lookup_t;
 
 /*
  * Lower-tier fetch: write the row of keys[i] to rows[i*dim .. i*dim+dim) for i < n.  keys and rows
- * are host pointers (pinned, owned by the lookup object); keys are distinct.  Called on the thread
+ * are host pointers (pinned, owned by the lookup object); keys are distinct, in no particular
+ * order.  Called on the thread
  * that calls hps_lookup (synchronous insertion) or on the object's background thread.
  */
 typedef void (*hps_fetch_fn)(void *user, const int64_t *keys, size_t n, float *rows);
@@ -32,7 +35,7 @@ typedef void (*hps_fetch_fn)(void *user, const int64_t *keys, size_t n, float *r
  * cache           the cache to serve from; it must allow concurrent writers
  *                 (hps_cache_set_concurrent_writers(cache, 1), the default) because background
  *                 inserts overlap later queries.
- * max_batch       largest n a lookup call may pass.
+ * max_batch       largest n a lookup call may pass (1 .. 2^31 - 1).
  * hit_threshold   t of Alg. 1: hit rate < t selects synchronous insertion.  0 = always
  *                 asynchronous, anything above 1 = always synchronous.
  * default_row     [host, dim fp32] vector handed out for missing keys in asynchronous mode.

@@ -30,6 +30,7 @@ EXPORTS = (
     "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
     "hps_cache_flags", "hps_cache_debug_set_seq",
     "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
+    "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
 )
 
 # lower-tier fetch callback of hps_lookup.h: (user, keys*, n, rows*)
@@ -59,6 +60,8 @@ def load_library():
     lib.hps_last_error.argtypes = []
     lib.hps_lookup_last_error.restype = C.c_char_p
     lib.hps_lookup_last_error.argtypes = []
+    lib.hps_dedup_last_error.restype = C.c_char_p
+    lib.hps_dedup_last_error.argtypes = []
     sigs = {
         "hps_cache_create": [sz, u32, u32, C.POINTER(vp)],
         "hps_cache_create_policy": [sz, u32, u32, C.c_int, C.POINTER(vp)],
@@ -70,6 +73,10 @@ def load_library():
         "hps_lookup": [vp, vp, sz, vp, C.POINTER(C.c_float), C.POINTER(C.c_int), vp],
         "hps_lookup_drain": [vp],
         "hps_lookup_destroy": [vp],
+        "hps_dedup_create": [sz, C.POINTER(vp)],
+        "hps_dedup_destroy": [vp],
+        "hps_dedup": [vp, vp, sz, vp, vp, vp, vp],
+        "hps_expand_rows": [vp, vp, sz, u32, vp, vp],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
         "hps_cache_insert": [vp, vp, vp, sz, vp],
@@ -265,3 +272,35 @@ def hps_lookup_drain(lookup) -> None:
 
 def hps_lookup_destroy(lookup) -> None:
     _check_lookup(load_library().hps_lookup_destroy(lookup))
+
+
+# ---- hps_dedup.h: Q* = dedup(Q) (Sec. 2.2) and the row expansion after the lookup of Q*
+
+def _check_dedup(status):
+    if status != HPS_OK:
+        raise HpsError(status, load_library().hps_dedup_last_error().decode())
+
+
+def hps_dedup_last_error() -> str:
+    return load_library().hps_dedup_last_error().decode()
+
+
+def hps_dedup_create(max_n: int) -> int:
+    h = C.c_void_p()
+    _check_dedup(load_library().hps_dedup_create(max_n, C.byref(h)))
+    return h.value
+
+
+def hps_dedup_destroy(session) -> None:
+    _check_dedup(load_library().hps_dedup_destroy(session))
+
+
+def hps_dedup(session, keys, n, unique_keys, inverse, n_unique, stream=None) -> None:
+    _check_dedup(load_library().hps_dedup(
+        session, _ptr(keys, torch.int64), n, _ptr(unique_keys, torch.int64), _ptr(inverse, torch.int32),
+        _ptr(n_unique, torch.int32), _stream(stream)))
+
+
+def hps_expand_rows(rows, inverse, n, dim, out, stream=None) -> None:
+    _check_dedup(load_library().hps_expand_rows(
+        _ptr(rows, torch.float32), _ptr(inverse, torch.int32), n, dim, _ptr(out, torch.float32), _stream(stream)))

@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRCS = [os.path.join(HERE, "csrc", "hps_cache.hip"), os.path.join(HERE, "csrc", "hps_lookup.hip")]
+SRCS = [os.path.join(HERE, "csrc", f) for f in ("hps_cache.hip", "hps_lookup.hip", "hps_dedup.hip")]
 LIB = os.path.join(HERE, "libhps_cache.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

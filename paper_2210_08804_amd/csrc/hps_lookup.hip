@@ -12,9 +12,9 @@
 #include <new>
 #include <string>
 #include <thread>
-#include <unordered_map>
 #include <vector>
 
+#include "hps_dedup.h"
 #include "hps_lookup.h"
 
 namespace {
@@ -38,8 +38,8 @@ __global__ void place_rows_kernel(float *out, const uint32_t *__restrict__ idx,
 }
 
 struct Task {                 // one queued asynchronous insertion
-    int64_t   *h_keys;        // pinned, the batch's missing keys (with duplicates)
-    uint32_t   m;
+    int64_t   *h_keys;        // pinned, the batch's distinct missing keys
+    uint32_t   m;             // how many
     hipEvent_t ready;         // the device-to-host copy of h_keys has finished
 };
 
@@ -53,19 +53,19 @@ struct hps_lookup_session {
     float        threshold;
     hps_fetch_fn fetch;
     void        *user;
+    hps_dedup_t *dd;          // dedup of the miss list before it leaves the device (Sec. 2.2)
     // workspace (the paper's ws): device side
-    uint32_t *d_miss_idx, *d_n_miss, *d_inv;
+    uint32_t *d_miss_idx, *d_n_miss, *d_inv, *d_n_unique;
     int64_t  *d_miss_keys, *d_ukeys;
     float    *d_rows, *d_default;
     // pinned host side
-    uint32_t *h_n_miss, *h_inv;
-    int64_t  *h_keys, *h_ukeys;
+    uint32_t *h_n_miss, *h_n_unique;
+    int64_t  *h_ukeys;
     float    *h_rows;
     // background insertion
     hipStream_t side;
     int64_t  *bg_d_ukeys;
     float    *bg_d_rows, *bg_h_rows;
-    int64_t  *bg_h_ukeys;
     std::thread worker;
     std::mutex mu;
     std::condition_variable cv, cv_idle;
@@ -92,26 +92,6 @@ hps_status_t lfail(hps_status_t code, const std::string &msg) {
                          std::string(#expr) + ": " + hipGetErrorString(e_));                 \
     } while (0)
 
-// Distinct keys of a miss list, in first-occurrence order, and for every entry the index of its
-// key among them (the paper deduplicates before going to the lower tiers, Sec. 2.2).
-uint32_t dedup_host(const int64_t *keys, uint32_t m, int64_t *ukeys, uint32_t *inv) {
-    std::unordered_map<int64_t, uint32_t> seen;
-    seen.reserve(m * 2);
-    uint32_t u = 0;
-    for (uint32_t j = 0; j < m; ++j) {
-        auto it = seen.find(keys[j]);
-        if (it == seen.end()) {
-            seen.emplace(keys[j], u);
-            ukeys[u] = keys[j];
-            if (inv) inv[j] = u;
-            ++u;
-        } else if (inv) {
-            inv[j] = it->second;
-        }
-    }
-    return u;
-}
-
 void launch_place(float *out, const uint32_t *idx, const uint32_t *src, const float *rows, uint32_t m,
                   uint32_t d, hipStream_t st) {
     const uint64_t total = (uint64_t)m * (d / 4);
@@ -136,9 +116,9 @@ void worker_main(hps_lookup_session *L) {
         std::string err;
         hipError_t e = hipEventSynchronize(t.ready);
         if (e == hipSuccess) {
-            const uint32_t u = dedup_host(t.h_keys, t.m, L->bg_h_ukeys, nullptr);
-            L->fetch(L->user, L->bg_h_ukeys, u, L->bg_h_rows);
-            e = hipMemcpyAsync(L->bg_d_ukeys, L->bg_h_ukeys, (size_t)u * sizeof(int64_t), hipMemcpyHostToDevice, L->side);
+            const uint32_t u = t.m;
+            L->fetch(L->user, t.h_keys, u, L->bg_h_rows);
+            e = hipMemcpyAsync(L->bg_d_ukeys, t.h_keys, (size_t)u * sizeof(int64_t), hipMemcpyHostToDevice, L->side);
             if (e == hipSuccess)
                 e = hipMemcpyAsync(L->bg_d_rows, L->bg_h_rows, (size_t)u * L->dim * sizeof(float),
                                    hipMemcpyHostToDevice, L->side);
@@ -159,12 +139,12 @@ void worker_main(hps_lookup_session *L) {
 }
 
 void free_all(hps_lookup_session *L) {
-    (void)hipFree(L->d_miss_idx); (void)hipFree(L->d_n_miss); (void)hipFree(L->d_inv);
+    (void)hps_dedup_destroy(L->dd);
+    (void)hipFree(L->d_miss_idx); (void)hipFree(L->d_n_miss); (void)hipFree(L->d_inv); (void)hipFree(L->d_n_unique);
     (void)hipFree(L->d_miss_keys); (void)hipFree(L->d_ukeys); (void)hipFree(L->d_rows); (void)hipFree(L->d_default);
     (void)hipFree(L->bg_d_ukeys); (void)hipFree(L->bg_d_rows);
-    (void)hipHostFree(L->h_n_miss); (void)hipHostFree(L->h_inv); (void)hipHostFree(L->h_keys);
+    (void)hipHostFree(L->h_n_miss); (void)hipHostFree(L->h_n_unique);
     (void)hipHostFree(L->h_ukeys); (void)hipHostFree(L->h_rows); (void)hipHostFree(L->bg_h_rows);
-    (void)hipHostFree(L->bg_h_ukeys);
     for (int64_t *p : L->free_key_bufs) (void)hipHostFree(p);
     if (L->side) (void)hipStreamDestroy(L->side);
 }
@@ -181,25 +161,25 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     uint32_t dim = 0;
     if (hps_cache_info(cache, nullptr, nullptr, &dim) != HPS_OK) return lfail(HPS_ERR_INVALID_ARG, "invalid cache handle");
     if (!fetch || !default_row) return lfail(HPS_ERR_INVALID_ARG, "fetch and default_row are required");
-    if (max_batch == 0 || max_batch >= (1ull << 32)) return lfail(HPS_ERR_INVALID_ARG, "max_batch must be in [1, 2^32)");
+    if (max_batch == 0 || max_batch >= (1ull << 31)) return lfail(HPS_ERR_INVALID_ARG, "max_batch must be in [1, 2^31)");
     hps_lookup_session *L = new (std::nothrow) hps_lookup_session();
     if (!L) return lfail(HPS_ERR_OOM, "host allocation failed");
     L->cache = cache; L->max_batch = max_batch; L->dim = dim; L->threshold = hit_threshold;
     L->fetch = fetch; L->user = user;
-    L->d_miss_idx = L->d_n_miss = L->d_inv = nullptr; L->d_miss_keys = L->d_ukeys = nullptr;
-    L->d_rows = L->d_default = nullptr; L->h_n_miss = L->h_inv = nullptr; L->h_keys = L->h_ukeys = nullptr;
+    L->dd = nullptr;
+    L->d_miss_idx = L->d_n_miss = L->d_inv = L->d_n_unique = nullptr; L->d_miss_keys = L->d_ukeys = nullptr;
+    L->d_rows = L->d_default = nullptr; L->h_n_miss = L->h_n_unique = nullptr; L->h_ukeys = nullptr;
     L->h_rows = nullptr; L->side = nullptr; L->bg_d_ukeys = nullptr; L->bg_d_rows = L->bg_h_rows = nullptr;
-    L->bg_h_ukeys = nullptr;
     const size_t nb = max_batch, rowb = (size_t)dim * sizeof(float);
     hipError_t e = hipGetDevice(&L->device);
     auto dev = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
     auto pin = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipHostMalloc(p, bytes, hipHostMallocDefault); };
     dev((void **)&L->d_miss_idx, nb * 4); dev((void **)&L->d_n_miss, 4); dev((void **)&L->d_inv, nb * 4);
+    dev((void **)&L->d_n_unique, 4);
     dev((void **)&L->d_miss_keys, nb * 8); dev((void **)&L->d_ukeys, nb * 8); dev((void **)&L->d_rows, nb * rowb);
     dev((void **)&L->d_default, rowb); dev((void **)&L->bg_d_ukeys, nb * 8); dev((void **)&L->bg_d_rows, nb * rowb);
-    pin((void **)&L->h_n_miss, 4); pin((void **)&L->h_inv, nb * 4); pin((void **)&L->h_keys, nb * 8);
+    pin((void **)&L->h_n_miss, 4); pin((void **)&L->h_n_unique, 4);
     pin((void **)&L->h_ukeys, nb * 8); pin((void **)&L->h_rows, nb * rowb); pin((void **)&L->bg_h_rows, nb * rowb);
-    pin((void **)&L->bg_h_ukeys, nb * 8);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipMemcpy(L->d_default, default_row, rowb, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -209,6 +189,12 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
         free_all(L);
         delete L;
         return lfail(code, msg);
+    }
+    if (const hps_status_t ds = hps_dedup_create(max_batch, &L->dd)) {
+        const std::string msg = std::string("hps_lookup_create: ") + hps_dedup_last_error();
+        free_all(L);
+        delete L;
+        return lfail(ds, msg);
     }
     L->worker = std::thread(worker_main, L);
     *out_lookup = L;
@@ -244,13 +230,16 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     if (rate < L->threshold) {
         // synchronous insertion: ParServerLookup(missing keys), EmbCacheInsert, E_Q <- fetched vectors
         if (was_synchronous) *was_synchronous = 1;
-        LK_TRY(hipMemcpyAsync(L->h_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
+        // the lower tiers see each missing key once (Sec. 2.2): dedup on the device, only the
+        // distinct keys travel to the host; the map from miss-list entries to them stays here
+        if (hps_dedup(L->dd, L->d_miss_keys, m, L->d_ukeys, L->d_inv, L->d_n_unique, st) != HPS_OK)
+            return lfail(HPS_ERR_DEVICE, std::string("dedup: ") + hps_dedup_last_error());
+        LK_TRY(hipMemcpyAsync(L->h_n_unique, L->d_n_unique, 4, hipMemcpyDeviceToHost, st));
+        LK_TRY(hipMemcpyAsync(L->h_ukeys, L->d_ukeys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
         LK_TRY(hipStreamSynchronize(st));
-        const uint32_t u = dedup_host(L->h_keys, m, L->h_ukeys, L->h_inv);
+        const uint32_t u = *L->h_n_unique;
         L->fetch(L->user, L->h_ukeys, u, L->h_rows);
-        LK_TRY(hipMemcpyAsync(L->d_ukeys, L->h_ukeys, (size_t)u * 8, hipMemcpyHostToDevice, st));
         LK_TRY(hipMemcpyAsync(L->d_rows, L->h_rows, (size_t)u * L->dim * sizeof(float), hipMemcpyHostToDevice, st));
-        LK_TRY(hipMemcpyAsync(L->d_inv, L->h_inv, (size_t)m * 4, hipMemcpyHostToDevice, st));
         launch_place(out, L->d_miss_idx, L->d_inv, L->d_rows, m, L->dim, st);
         LK_TRY(hipGetLastError());
         if (hps_cache_insert(L->cache, L->d_ukeys, L->d_rows, u, st) != HPS_OK)
@@ -263,8 +252,9 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     // asynchronous insertion: default vectors now, the real rows reach the cache later
     launch_place(out, L->d_miss_idx, nullptr, L->d_default, m, L->dim, st);
     LK_TRY(hipGetLastError());
+    if (hps_dedup(L->dd, L->d_miss_keys, m, L->d_ukeys, L->d_inv, L->d_n_unique, st) != HPS_OK)
+        return lfail(HPS_ERR_DEVICE, std::string("dedup: ") + hps_dedup_last_error());
     Task t;
-    t.m = m;
     {
         std::lock_guard<std::mutex> lk(L->mu);
         if (!L->free_key_bufs.empty()) {
@@ -276,10 +266,12 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     }
     if (!t.h_keys) LK_TRY(hipHostMalloc((void **)&t.h_keys, L->max_batch * 8, hipHostMallocDefault));
     LK_TRY(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
-    LK_TRY(hipMemcpyAsync(t.h_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
+    LK_TRY(hipMemcpyAsync(L->h_n_unique, L->d_n_unique, 4, hipMemcpyDeviceToHost, st));
+    LK_TRY(hipMemcpyAsync(t.h_keys, L->d_ukeys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
     LK_TRY(hipEventRecord(t.ready, st));
-    // the workspace's miss list is read by that copy; wait for it before the next call reuses it
+    // the workspace is read by those copies; wait for them before the next call reuses it
     LK_TRY(hipStreamSynchronize(st));
+    t.m = *L->h_n_unique;
     {
         std::lock_guard<std::mutex> lk(L->mu);
         L->queue.push_back(t);

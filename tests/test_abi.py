@@ -60,6 +60,13 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.hps_lookup(None, None, 0, None, None, None, None) == -1
     assert lib.hps_lookup_drain(None) == -1 and lib.hps_lookup_destroy(None) == -1
     assert len(lib.hps_lookup_last_error()) > 0
+    assert lib.hps_dedup_create(0, C.byref(h)) == -1 and lib.hps_dedup_create(1 << 31, C.byref(h)) == -1
+    assert lib.hps_dedup_create(16, None) == -1 and lib.hps_dedup_destroy(None) == 0
+    assert lib.hps_dedup(None, None, 0, None, None, None, None) == -1
+    assert lib.hps_expand_rows(None, None, 5, 6, None, None) == -1       # dim not a multiple of 4
+    assert lib.hps_expand_rows(None, None, 5, 8, None, None) == -1       # NULL pointers
+    assert lib.hps_expand_rows(None, None, 0, 8, None, None) == 0        # nothing to do
+    assert len(lib.hps_dedup_last_error()) > 0
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
@@ -74,7 +81,7 @@ def test_headers_are_plain_c(tmp_path):
     """The boundary is a C ABI: both headers must compile as C99 with no HIP or C++ in sight."""
     import subprocess
     src = tmp_path / "use.c"
-    src.write_text('#include "hps_lookup.h"\n#include "hps_cache.h"\n'
+    src.write_text('#include "hps_lookup.h"\n#include "hps_dedup.h"\n#include "hps_cache.h"\n'
                    "int main(void) { hps_cache_t *c = 0; hps_lookup_t *l = 0; (void)c; (void)l; return HPS_OK; }\n")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                     "-I", os.path.join(ROOT, "include"), str(src)], check=True)

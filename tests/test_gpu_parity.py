@@ -227,6 +227,38 @@ def test_key_given_very_many_times_does_not_starve_its_set():
         compare_query(gc, oc, keys[:4096])
 
 
+@pytest.mark.parametrize("dtype,dim", [(torch.bfloat16, 128), (torch.float16, 64), (torch.float16, 200)])
+def test_half_precision_rows_travel_as_opaque_words(dtype, dim):
+    """Rows are bit patterns to every kernel, so a table of 16-bit values is a cache of dim/2
+    32-bit words: the caller reinterprets its tensors (a view, no conversion)."""
+    S, W = 1024, 8
+    words = dim // 2
+    keys = np.unique(inputs.uniform_keys(1500, 1 << 32, 31))
+    table = torch.randn(len(keys), dim, generator=torch.Generator().manual_seed(5)).to(dtype)
+    as_words = table.view(torch.float32).numpy().view(np.uint32)
+    assert as_words.shape == (len(keys), words)
+    with DeviceCache(S * W, W, words) as gc:
+        oc = OracleCache(S * W, W, words)
+        insert_both(gc, oc, keys, as_words)
+        q = np.concatenate([keys[::3], keys[:100] + (1 << 40)])
+        dk = torch.from_numpy(q).cuda()
+        out = torch.zeros(len(q), dim, dtype=dtype, device="cuda")
+        mi = torch.empty(len(q), dtype=torch.int32, device="cuda")
+        mk = torch.empty(len(q), dtype=torch.int64, device="cuda")
+        nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.hps_cache_query(gc.h, dk, len(q), out.view(torch.float32), mi, mk, nm)
+        torch.cuda.synchronize()
+        exp = np.zeros((len(q), words), dtype=np.uint32)
+        _, omi, _ = oc.query(q, exp)
+        assert int(nm.item()) == len(omi) >= 100
+        assert (out.cpu().view(torch.float32).numpy().view(np.uint32) == exp).all()
+        hit = np.ones(len(q), dtype=bool)
+        hit[omi] = False
+        pos = {int(k): i for i, k in enumerate(keys.tolist())}
+        src = torch.tensor([pos[int(k)] for k in q[hit]])
+        assert torch.equal(out.cpu()[torch.from_numpy(hit)], table[src])      # the very same 16-bit values
+
+
 def test_one_set_overflow_keeps_invariants():
     # all keys of the batch fall into one set of a 4-way cache: far more than W new keys
     S, W, d = 8, 4, 8
