@@ -32,6 +32,7 @@ constexpr int64_t  kEmpty      = INT64_MIN;
 constexpr int      kBlock      = 256;          // threads per work-group: 4 waves of 64
 constexpr int      kWave       = 64;
 constexpr int      kWavesPerWg = kBlock / kWave;
+constexpr int      kInsertKpw  = 16;           // keys per wave of the insert kernel
 constexpr uint32_t kRing       = 1024;         // counter words, one per stream seen (see counter_word)
 constexpr uint64_t kMagic      = 0x4850534341434845ull;
 // Every loop that waits for another kernel's writer to let go of a set gives up after this many
@@ -678,12 +679,13 @@ struct WriteArgs {
 // already there.  Lanes that did not get their set search it without owning it before every
 // further attempt.  No lane ever waits while the wave owns a set: each round every pending lane
 // tries once, the owners' rows are copied by the whole wave, the sets are released, and the
-// others try again.  Small batches use KPW = 16 so that four times as many waves share the row
-// copies.
+// others try again.  KPW = 16: four times as many waves as keys / 64 share the row copies, and a
+// wave's chain of dependent memory round trips is two copy groups long instead of eight.
 template <int W, int KPW>
 __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
     __shared__ uint64_t s_dst[kWavesPerWg][kWave];
     __shared__ uint32_t s_srcrow[kWavesPerWg][kWave];
+    __shared__ uint32_t s_owner[kWavesPerWg][kWave * 2];
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
@@ -703,7 +705,20 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
         const bool mine = lane < KPW && i < n;
         const int64_t key = mine ? a.keys[i] : kEmpty;
         bool pending = mine && !is_reserved(key);
-        const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
+        const uint64_t h = mix64((uint64_t)key);
+        const uint32_t hs = (uint32_t)(h >> 32);
+        const uint32_t set = pending ? (tb.smask ? (hs & tb.smask) : (hs % tb.S)) : 0u;
+
+        // Copies of a key inside this wave: all of them write their lane number into the key's
+        // hash slot, the one whose number stays carries the key, the others drop out (Alg. 3
+        // ignores a key that is already there, so only one copy can ever take effect).  A slot
+        // shared by different keys thins nothing.
+        if (pending) s_owner[wave][h & (kWave * 2 - 1)] = (uint32_t)lane;
+        wave_lds_fence();
+        const int o = pending ? (int)s_owner[wave][h & (kWave * 2 - 1)] : lane;
+        const int64_t ko = shfl64(key, o);
+        if (pending && o != lane && ko == key) pending = false;
+        wave_lds_fence();
 
         uint32_t rounds = 0;
         while (__ballot(pending)) {
@@ -1133,7 +1148,9 @@ hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, 
     a.n = (uint32_t)n;
     a.g = make_geom(c->d);
     // insert: 16 keys per wave while 64 would leave fewer than 8 waves per CU
-    const uint32_t kpw = (kInsert && n < (size_t)c->n_cus * 8 * kWave) ? 16u : (uint32_t)kWave;
+    // insert: 16 keys per wave (measured best from 1 K to 1 M keys: 8, 32 and 64 are 3-45 % slower)
+    // update: 64 keys per wave (16 and 32 measured 10 % slower on 2^18 rows, 9-55 % on a 40 GB refresh)
+    const uint32_t kpw = kInsert ? (uint32_t)kInsertKpw : (uint32_t)kWave;
     const uint64_t tiles = (n + kpw - 1) / kpw;
     uint64_t blocks = (tiles + kWavesPerWg - 1) / kWavesPerWg;
     if (blocks > (1u << 16)) blocks = 1u << 16;
@@ -1141,8 +1158,7 @@ hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, 
     switch (c->W) {
 #define HPS_CASE(w)                                                                         \
     case w:                                                                                 \
-        if (kInsert && kpw == 16) hipLaunchKernelGGL((insert_kernel<w, 16>), grid, block, 0, st, a); \
-        else if (kInsert) hipLaunchKernelGGL((insert_kernel<w, 64>), grid, block, 0, st, a); \
+        if (kInsert) hipLaunchKernelGGL((insert_kernel<w, kInsertKpw>), grid, block, 0, st, a); \
         else hipLaunchKernelGGL((update_kernel<w>), grid, block, 0, st, a);                 \
         break;
         HPS_CASE(1) HPS_CASE(2) HPS_CASE(4) HPS_CASE(8) HPS_CASE(16) HPS_CASE(32) HPS_CASE(64)
