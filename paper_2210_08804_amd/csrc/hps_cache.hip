@@ -356,7 +356,7 @@ struct QueryArgs {
     uint32_t      *miss_idx;
     int64_t       *miss_keys;
     uint32_t      *n_miss;
-    uint64_t      *slot;        // per-call counter word: low 32 bits = misses so far, high 32 = tiles done
+    uint64_t      *slot;        // the stream's counter word: low 32 bits = misses so far, high 32 = tiles done
     uint32_t       B;           // keys per table
     uint32_t       kpw;         // keys per worker wave (<= 64): lanes kpw..63 of a worker wave stay idle
     uint32_t       tiles_per_table;
