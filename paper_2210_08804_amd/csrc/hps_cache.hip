@@ -33,7 +33,7 @@ constexpr int      kBlock      = 256;          // threads per work-group: 4 wave
 constexpr int      kWave       = 64;
 constexpr int      kWavesPerWg = kBlock / kWave;
 constexpr int      kInsertKpw  = 16;           // keys per wave of the insert kernel
-constexpr uint32_t kRing       = 1024;         // counter words, one per stream seen (see counter_word)
+constexpr uint32_t kRing       = 1024;         // counter words per half of the pool (see counter_word)
 constexpr uint64_t kMagic      = 0x4850534341434845ull;
 // Every loop that waits for another kernel's writer to let go of a set gives up after this many
 // rounds (a held set is released within microseconds; this many rounds take about a second) and
@@ -1026,9 +1026,10 @@ struct hps_cache {
     float    *V;
     uint32_t *ctr;
     uint32_t *seq;
-    uint64_t *ring;                       // kRing counter words, all zero between calls
+    uint64_t *ring;                       // 2 * kRing counter words, all zero between calls
     std::mutex word_mu;
     std::unordered_map<void *, uint32_t> word_of_stream;
+    uint32_t word_half;                   // which half of `ring` is being handed out
     std::atomic<int> concurrent_writers;
     std::atomic<int> query_dedup;
     int      policy;                      // HPS_POLICY_*
@@ -1067,13 +1068,21 @@ Table table_of(const hps_cache *c) {
 
 // Counter word of query/dump calls on `stream`.  Calls on one stream run one after the other and
 // each leaves its word at zero, so they can share one; calls on different streams may overlap and
-// get different words (the first kRing streams seen; beyond that words are shared modulo kRing).
+// get different words.  The pool is two halves of kRing words: streams are given words of the
+// current half in order of first sight; when a half is used up (kRing different stream handles,
+// e.g. a caller that keeps creating streams) the table is forgotten and the other half is
+// handed out, so a kernel still running with a word of the old half is never disturbed.
 // A kernel captured into a graph keeps the word of the stream it was captured on.
 uint64_t *counter_word(hps_cache *c, void *stream) {
     std::lock_guard<std::mutex> lk(c->word_mu);
     auto it = c->word_of_stream.find(stream);
-    if (it == c->word_of_stream.end())
-        it = c->word_of_stream.emplace(stream, (uint32_t)(c->word_of_stream.size() % kRing)).first;
+    if (it == c->word_of_stream.end()) {
+        if (c->word_of_stream.size() >= kRing) {
+            c->word_of_stream.clear();
+            c->word_half ^= 1u;
+        }
+        it = c->word_of_stream.emplace(stream, c->word_half * kRing + (uint32_t)c->word_of_stream.size()).first;
+    }
     return c->ring + it->second;
 }
 
@@ -1214,7 +1223,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->S = capacity / ways;
     c->W = ways;
     c->d = dim;
-    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr;
+    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr; c->word_half = 0;
     c->policy = policy;
     c->g.store(0);
     c->concurrent_writers.store(1);
@@ -1228,7 +1237,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     if (e == hipSuccess) e = hipMalloc(&c->V, capacity * (size_t)dim * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&c->ctr, c->S * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->seq, c->S * sizeof(uint32_t));
-    if (e == hipSuccess) e = hipMalloc(&c->ring, kRing * sizeof(uint64_t));
+    if (e == hipSuccess) e = hipMalloc(&c->ring, 2 * kRing * sizeof(uint64_t));
     if (e == hipSuccess) e = hipMalloc(&c->flags, sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemsetAsync(c->flags, 0, sizeof(uint32_t), 0);
     if (e == hipSuccess && policy == HPS_POLICY_LRU) {
@@ -1242,7 +1251,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     if (e == hipSuccess) e = hipMemsetAsync(c->V, 0, capacity * (size_t)dim * sizeof(float), 0);
     if (e == hipSuccess) e = hipMemsetAsync(c->ctr, 0, c->S * sizeof(uint32_t), 0);
     if (e == hipSuccess) e = hipMemsetAsync(c->seq, 0, c->S * sizeof(uint32_t), 0);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ring, 0, kRing * sizeof(uint64_t), 0);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ring, 0, 2 * kRing * sizeof(uint64_t), 0);
     if (e == hipSuccess) e = hipStreamSynchronize(0);
     if (e != hipSuccess) {
         const hps_status_t code = e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE;

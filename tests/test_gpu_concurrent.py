@@ -130,3 +130,48 @@ def test_insert_overlapping_queries_keeps_rows_whole():
         oc = OracleCache(S * W, W, d)
         check_state_invariants(gk, gctr, gv, oc.set_of,
                                expect_row=lambda k: [inputs.backing_rows(np.array([k]), d, 0).view(np.uint32)[0]])
+
+
+def test_more_stream_handles_than_counter_words():
+    """Every stream that queries gets a counter word of its own; a caller that goes through more
+    stream handles than the pool has words must still get correct miss lists on all of them."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipStreamCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+    hip.hipStreamDestroy.argtypes = [C.c_void_p]
+    S, W, d, n = 64, 8, 16, 300
+    keys = inputs.uniform_keys(n, 500, 9)
+    with DeviceCache(S * W, W, d, concurrent_writers=False) as gc:
+        oc = OracleCache(S * W, W, d)
+        resident = np.unique(keys)[::2].copy()
+        gc.insert(resident, inputs.backing_rows(resident, d))
+        oc.insert(resident, inputs.backing_rows(resident, d).view(np.uint32))
+        exp_out = np.full((n, d), SENTINEL, dtype=np.uint32)
+        _, exp_mi, _ = oc.query(keys, exp_out)
+        dk = torch.from_numpy(keys).cuda()
+        streams, results = [], []
+        try:
+            for i in range(1100):
+                h = C.c_void_p()
+                assert hip.hipStreamCreateWithFlags(C.byref(h), 1) == 0          # non-blocking
+                streams.append(h)
+                st = torch.cuda.ExternalStream(h.value)
+                out = torch.full((n, d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32)
+                mi = torch.empty(n, dtype=torch.int32, device="cuda")
+                mk = torch.empty(n, dtype=torch.int64, device="cuda")
+                nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+                torch.cuda.current_stream().synchronize()                        # the fills above are done
+                B.hps_cache_query(gc.h, dk, n, out, mi, mk, nm, st)
+                results.append((out, mi, nm))
+                if i % 100 == 99 or i >= 1020:                                   # around the switch of pools, and samples
+                    torch.cuda.synchronize()
+                    for o, m_i, n_m in results:
+                        m = int(n_m.item())
+                        assert m == len(exp_mi)
+                        assert (np.sort(m_i[:m].cpu().numpy().view(np.uint32)) == exp_mi).all()
+                        assert (o.view(torch.int32).cpu().numpy().view(np.uint32) == exp_out).all()
+                    results.clear()
+        finally:
+            torch.cuda.synchronize()
+            for h in streams:
+                hip.hipStreamDestroy(h)
