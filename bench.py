@@ -228,14 +228,11 @@ def dedup_lookup(a, np, torch, B, inputs):
     t_direct = timed(lambda s: B.hps_cache_query(h, keys[s], n, out, mi, mk, nm))
     t_dedup = timed(lambda s: B.hps_dedup(dd, keys[s], n, uk, inv, nu[s:s + 1]))
     n_u = nu[warm:].cpu().numpy()
-    # the distinct-key count is known on the host only after a copy; the device-side path below
-    # queries with the upper bound of the measured batches instead (a real caller would read it
-    # back or size by the batch): here each step uses its own count, read once beforehand
     counts = nu.cpu().numpy().tolist()
 
-    def path(s):
+    def path(s):                                   # no host round trip: the query reads the count on the device
         B.hps_dedup(dd, keys[s], n, uk, inv, nu[s:s + 1])
-        B.hps_cache_query(h, uk, counts[s], urows, mi, mk, nm)
+        B.hps_cache_query_dn(h, uk, n, nu[s:s + 1], urows, mi, mk, nm)
         B.hps_expand_rows(urows, inv, n, d, out)
 
     t_path = timed(path)

@@ -222,6 +222,18 @@ hps_status_t hps_cache_insert_dn(hps_cache_t *cache, const int64_t *keys, const 
 hps_status_t hps_cache_update_dn(hps_cache_t *cache, const int64_t *keys, const float *vals,
                                  size_t n_max, const uint32_t *n_dev, void *stream);
 
+/*
+ * Query (Sec. 4.2, Alg. 2) whose batch length is read on the device: positions
+ * 0 .. min(n_max, *n_dev) - 1 are looked up exactly as by hps_cache_query, the others are neither
+ * read as keys nor written in `out` nor reported as misses.  keys must be readable up to n_max
+ * entries; out / miss_idx / miss_keys are sized for n_max.  Lets a query follow a device-side
+ * producer of its keys (the distinct keys of hps_dedup.h, Sec. 2.2) without a host round trip.
+ * n_dev [device, one uint32, 4-byte aligned] must not be NULL.
+ */
+hps_status_t hps_cache_query_dn(hps_cache_t *cache, const int64_t *keys, size_t n_max,
+                                const uint32_t *n_dev, float *out, uint32_t *miss_idx,
+                                int64_t *miss_keys, uint32_t *n_miss, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

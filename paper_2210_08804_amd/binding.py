@@ -28,7 +28,7 @@ EXPORTS = (
     "hps_cache_export", "hps_cache_import", "hps_cache_dump", "hps_cache_query_multi",
     "hps_backing_fetch", "hps_cache_insert_dn", "hps_cache_update_dn", "hps_cache_set_query_dedup",
     "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
-    "hps_cache_flags", "hps_cache_debug_set_seq",
+    "hps_cache_flags", "hps_cache_debug_set_seq", "hps_cache_query_dn",
     "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
     "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
 )
@@ -90,6 +90,7 @@ def load_library():
         "hps_cache_query_multi": [C.POINTER(vp), u32, vp, sz, vp, vp, vp, vp, vp],
         "hps_backing_fetch": [vp, sz, vp, u32, u32, vp, vp, vp, vp],
         "hps_cache_insert_dn": [vp, vp, vp, sz, vp, vp],
+        "hps_cache_query_dn": [vp, vp, sz, vp, vp, vp, vp, vp, vp],
         "hps_cache_update_dn": [vp, vp, vp, sz, vp, vp],
     }
     for name, argtypes in sigs.items():
@@ -162,6 +163,12 @@ def hps_cache_query(handle, keys, n, out, miss_idx, miss_keys, n_miss, stream=No
     _check(load_library().hps_cache_query(
         handle, _ptr(keys, torch.int64), n, _ptr(out, torch.float32), _ptr(miss_idx, torch.int32),
         _ptr(miss_keys, torch.int64), _ptr(n_miss, torch.int32), _stream(stream)))
+
+
+def hps_cache_query_dn(handle, keys, n_max, n_dev, out, miss_idx, miss_keys, n_miss, stream=None) -> None:
+    _check(load_library().hps_cache_query_dn(
+        handle, _ptr(keys, torch.int64), n_max, _ptr(n_dev, torch.int32), _ptr(out, torch.float32),
+        _ptr(miss_idx, torch.int32), _ptr(miss_keys, torch.int64), _ptr(n_miss, torch.int32), _stream(stream)))
 
 
 def hps_cache_insert(handle, keys, vals, n, stream=None) -> None:

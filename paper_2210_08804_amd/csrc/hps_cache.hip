@@ -358,6 +358,7 @@ struct QueryArgs {
     uint32_t      *n_miss;
     uint64_t      *slot;        // the stream's counter word: low 32 bits = misses so far, high 32 = tiles done
     uint32_t       B;           // keys per table
+    const uint32_t *n_dev;      // optional: the real batch length (<= B) is read on the device (one table only)
     uint32_t       kpw;         // keys per worker wave (<= 64): lanes kpw..63 of a worker wave stay idle
     uint32_t       tiles_per_table;
     uint32_t       n_tiles;     // T * tiles_per_table (>= 1 even when B == 0)
@@ -402,10 +403,11 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
         if (wave < WPB) {
             const Table   &tb   = a.tab[t];
             const uint32_t b    = (lt * WPB + wave) * a.kpw + lane;
-            const bool     live = lane < (int)a.kpw && b < a.B;
+            const bool     inb  = lane < (int)a.kpw && b < a.B;
             const uint32_t pos  = t * a.B + b;         // position in keys/out (< 2^32 checked on host)
 
-            const int64_t key  = live ? a.keys[pos] : kEmpty;
+            const int64_t key  = inb ? a.keys[pos] : kEmpty;      // keys[0 .. B) is readable also when n_dev says less
+            const bool    live = inb && (!a.n_dev || b < *a.n_dev);
             const bool    want = live && !is_reserved(key);
             const uint32_t set = want ? set_of(key, tb.S, tb.smask) : 0u;
             bool hit;
@@ -548,9 +550,10 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
             const Table   &tb   = a.tab[t];
             const uint32_t tid  = (uint32_t)wave * a.kpw + (uint32_t)lane;   // index in the tile (idle lanes alias, unused)
             const uint32_t b    = lt * WPB * a.kpw + tid;
-            const bool     live = lane < (int)a.kpw && b < a.B;
+            const bool     inb  = lane < (int)a.kpw && b < a.B;
             const uint32_t pos  = pos0 + tid;
-            const int64_t  key  = live ? a.keys[pos] : kEmpty;
+            const int64_t  key  = inb ? a.keys[pos] : kEmpty;
+            const bool     live = inb && (!a.n_dev || b < *a.n_dev);
             const bool     want = live && !is_reserved(key);
             const uint64_t h    = mix64((uint64_t)key);
             const uint32_t hs   = (uint32_t)(h >> 32);
@@ -1322,9 +1325,9 @@ hps_status_t hps_cache_set_query_dedup(hps_cache_t *c, int enabled) {
     return HPS_OK;
 }
 
-hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables, const int64_t *keys,
-                                   size_t batch, float *out, uint32_t *miss_idx, int64_t *miss_keys,
-                                   uint32_t *n_miss, void *stream) {
+static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, const int64_t *keys,
+                               size_t batch, const uint32_t *n_dev, float *out, uint32_t *miss_idx,
+                               int64_t *miss_keys, uint32_t *n_miss, void *stream) {
     if (!caches || n_tables == 0 || n_tables > HPS_MAX_TABLES)
         return fail(HPS_ERR_INVALID_ARG, "n_tables must be in [1, HPS_MAX_TABLES]");
     for (uint32_t t = 0; t < n_tables; ++t) {
@@ -1354,6 +1357,7 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     a.n_miss = n_miss;
     a.slot = counter_word(caches[0], stream);
     a.B = (uint32_t)batch;
+    a.n_dev = n_dev;
     const QueryShape shape = query_shape(total);
     // Keys per worker wave: at most 64, trimmed so that the work-groups come out as a whole number
     // of rounds over the CUs (106,496 keys in tiles of 8 x 52 are exactly 256 work-groups; tiles of
@@ -1380,11 +1384,26 @@ hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables
     return launch_query(caches[0]->W, a, shape, coherent, dedup, static_cast<hipStream_t>(stream));
 }
 
+hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables, const int64_t *keys,
+                                   size_t batch, float *out, uint32_t *miss_idx, int64_t *miss_keys,
+                                   uint32_t *n_miss, void *stream) {
+    return query_call(caches, n_tables, keys, batch, nullptr, out, miss_idx, miss_keys, n_miss, stream);
+}
+
 hps_status_t hps_cache_query(hps_cache_t *c, const int64_t *keys, size_t n, float *out,
                              uint32_t *miss_idx, int64_t *miss_keys, uint32_t *n_miss, void *stream) {
     if (n >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n must be < 2^32");
     hps_cache_t *one[1] = {c};
-    return hps_cache_query_multi(one, 1, keys, n, out, miss_idx, miss_keys, n_miss, stream);
+    return query_call(one, 1, keys, n, nullptr, out, miss_idx, miss_keys, n_miss, stream);
+}
+
+hps_status_t hps_cache_query_dn(hps_cache_t *c, const int64_t *keys, size_t n_max, const uint32_t *n_dev,
+                                float *out, uint32_t *miss_idx, int64_t *miss_keys, uint32_t *n_miss,
+                                void *stream) {
+    if (n_max >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n_max must be < 2^32");
+    if (!n_dev || !aligned(n_dev, 4)) return fail(HPS_ERR_INVALID_ARG, "n_dev must be a 4-byte aligned device pointer");
+    hps_cache_t *one[1] = {c};
+    return query_call(one, 1, keys, n_max, n_dev, out, miss_idx, miss_keys, n_miss, stream);
 }
 
 hps_status_t hps_cache_insert(hps_cache_t *c, const int64_t *keys, const float *vals, size_t n, void *stream) {

@@ -344,6 +344,38 @@ def test_device_side_batch_length_variants():
         assert_same_state(gc.export(), oc)
 
 
+def test_query_with_device_side_batch_length():
+    """hps_cache_query_dn looks up min(n_max, *n_dev) positions; the rest of the buffers is
+    neither read as keys, nor written, nor reported."""
+    S, W, d, n_max = 512, 8, 32, 3000
+    with DeviceCache(S * W, W, d) as gc:
+        oc = OracleCache(S * W, W, d)
+        resident = np.unique(inputs.uniform_keys(2500, 6000, 41))
+        insert_both(gc, oc, resident, rows_u32(resident, d))
+        keys = inputs.uniform_keys(n_max, 6000, 42)
+        dk = torch.from_numpy(keys).cuda()
+        for n_real in [0, 1, 63, 64, 65, 1000, 2999, 3000, 5000]:
+            out = torch.full((n_max, d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32)
+            mi = torch.full((n_max,), -1, dtype=torch.int32, device="cuda")
+            mk = torch.full((n_max,), 0x5A5A5A5A, dtype=torch.int64, device="cuda")
+            nm = torch.full((1,), 777, dtype=torch.int32, device="cuda")
+            nd = torch.tensor([n_real], dtype=torch.int32, device="cuda")
+            B.hps_cache_query_dn(gc.h, dk, n_max, nd, out, mi, mk, nm)
+            torch.cuda.synchronize()
+            n = min(n_real, n_max)
+            exp = np.full((n_max, d), SENTINEL, dtype=np.uint32)
+            _, omi, omk = oc.query(keys[:n], exp[:n])
+            m = int(nm.item())
+            assert m == len(omi)
+            order = np.argsort(mi[:m].cpu().numpy().view(np.uint32))
+            assert (mi[:m].cpu().numpy().view(np.uint32)[order] == omi).all()
+            assert (mk[:m].cpu().numpy()[order] == omk).all()
+            assert (out.view(torch.int32).cpu().numpy().view(np.uint32) == exp).all()
+            assert (mi[m:] == -1).all() and (mk[m:] == 0x5A5A5A5A).all()
+        with pytest.raises(B.HpsError):
+            B.hps_cache_query_dn(gc.h, dk, n_max, None, out, mi, mk, nm)
+
+
 def test_query_multi_matches_per_table_oracles():
     d, W = 32, 8
     vocab = [50, 1000, 30000, 200]
