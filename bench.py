@@ -28,7 +28,7 @@ METRIC = "cache query Mkeys/s + achieved HBM GB/s (dim 128 fp32, Zipf keys)"
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--workload", choices=["query", "refresh", "stream", "multi", "concurrent", "dedup"], default="query",
+    p.add_argument("--workload", choices=["query", "refresh", "stream", "multi", "concurrent", "dedup", "write"], default="query",
                    help="query: the headline hot-cache query (default); refresh: dump every cached key, then "
                         "update every cached row (the paper's Table 3); stream: query + miss fill + insert per "
                         "step on a cold cache; multi: 26 tables in one launch; concurrent: queries on one "
@@ -251,6 +251,48 @@ def dedup_lookup(a, np, torch, B, inputs):
     print(json.dumps(res))
 
 
+def write_batches(a, np, torch, B, inputs):
+    """Insert and update in isolation: batches of `--samples x --features` (default 2^18 when
+    --samples is left at 4096: 10082 x 26 is rounded to 2^18) new keys into the hot-cache
+    geometry, then updates of the same keys.  A step is one insert call plus one update call."""
+    S, W, d = 1 << a.log2_sets, a.ways, a.dim
+    n = 1 << 18 if a.samples == 4096 else a.samples * a.features
+    steps = min(a.steps, (S * W) // n, 32)
+    h = B.hps_cache_create(S * W, W, d)
+    rows = torch.empty(n, d, dtype=torch.float32, device="cuda")
+    ids = torch.arange(n, dtype=torch.int64, device="cuda")
+    B.hps_backing_fetch(ids, n, d, 0, rows=rows)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_ins, t_upd = [], []
+    for c in range(steps):
+        k = ids + c * n
+        e0, e1, e2 = ev(), ev(), ev()
+        torch.cuda.synchronize()
+        e0.record()
+        B.hps_cache_insert(h, k, rows, n)
+        e1.record()
+        B.hps_cache_update(h, k, rows, n)
+        e2.record()
+        torch.cuda.synchronize()
+        t_ins.append(e0.elapsed_time(e1))
+        t_upd.append(e1.elapsed_time(e2))
+    ins_us, upd_us = float(np.median(t_ins)) * 1e3, float(np.median(t_upd)) * 1e3
+    row_b = 4 * d
+    alg_ins = n * (8 + 64 + 2 * row_b + 8 + 8)          # key, key line, row read + written, key + counter/word stores
+    res = {"metric": "insert + update of one batch, Mrows/s", "value": round(n / (ins_us + upd_us), 1), "unit": "Mrows/s",
+           "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": round((ins_us + upd_us) * 1e-3, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"insert of {n} new keys, then update of the same keys: {S} sets x {W} ways, dim {d}",
+                      "insert_us": round(ins_us, 1), "update_us": round(upd_us, 1),
+                      "insert_rows_GBps": round(n * 2 * row_b / ins_us / 1e3, 1), "update_rows_GBps": round(n * 2 * row_b / upd_us / 1e3, 1)},
+           "roofline": {"bound": "hbm", "achieved": round(alg_ins / ins_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(alg_ins / ins_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "insert_kernel<8,16>",
+                        "algorithmic_bytes_per_launch": alg_ins, "us_per_launch": round(ins_us, 1)}}
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    print(json.dumps(res))
+
+
 def multi_table(a, np, torch, B, inputs):
     """26 independent caches (vocabulary log-uniform in [1e3, 1e8], each cache 20 % of its vocabulary,
     at most 2^22 slots), one Zipf(1.05) key per table and sample, 131072 samples, one launch."""
@@ -380,6 +422,8 @@ def main():
         return concurrent(a, np, torch, B, inputs)
     if a.workload == "dedup":
         return dedup_lookup(a, np, torch, B, inputs)
+    if a.workload == "write":
+        return write_batches(a, np, torch, B, inputs)
 
     S, W, d = 1 << a.log2_sets, a.ways, a.dim
     slots = S * W
