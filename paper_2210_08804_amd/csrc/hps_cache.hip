@@ -3,8 +3,11 @@
 // Memory layout (all in HBM, owned by the cache):
 //   K   int64  [S][W]      keys, one 64-byte line per set at W = 8; EMPTY = INT64_MIN
 //   V   fp32   [S][W][d]   rows, 16-byte aligned, moved as opaque 128-bit chunks
-//   ctr uint32 [S]         victim counter: next way of the set = ctr mod W
-//   seq uint32 [S]         sequence word: odd while a writer owns the set (lock + seqlock)
+//   sc  uint32 [S][2]      one 8-byte word per set: {seq, ctr}
+//                            seq  sequence word: odd while a writer owns the set (lock + seqlock)
+//                            ctr  victim counter: next way of the set = ctr mod W
+//                          (together so that an insert gets both with its one 64-bit atomic and
+//                          lets go of both with one store; every read is a 128-byte request)
 //   T   uint32 [S][W]      access stamps, only for caches created with the LRU policy
 //
 // Paper passages: data model Sec. 4.1; Query Alg. 2; Replace Alg. 3; Update Alg. 4; Dump and
@@ -147,8 +150,7 @@ __device__ __forceinline__ void shared_st64(uint64_t *p, uint64_t v) {
 struct Table {                 // one cache as the kernels see it
     int64_t  *K;
     float    *V;
-    uint32_t *ctr;
-    uint32_t *seq;
+    uint32_t *sc;              // [S][2]: {sequence word, victim counter} of a set
     uint32_t  S;
     uint32_t  smask;           // S - 1 when S is a power of two, else 0
     uint32_t *T;               // [S][W] access stamps, LRU policy only (else nullptr)
@@ -158,6 +160,8 @@ struct Table {                 // one cache as the kernels see it
 
 // Row geometry shared by all copy loops: a row is C = d/4 chunks of 16 bytes; LPR lanes
 // cooperate on one row (16 B per lane, contiguous, so a wave load covers 64/LPR whole rows).
+__device__ __forceinline__ uint32_t *seq_of(const Table &tb, uint32_t set) { return tb.sc + 2ull * set; }
+
 struct RowGeom {
     uint32_t d;                // fp32 per row
     uint32_t C;                // 16-byte chunks per row
@@ -225,7 +229,7 @@ template <int U>
 __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *__restrict__ src,
                                                   float *__restrict__ dst, const uint64_t *srcRow,
                                                   const uint32_t *dstRow, const uint32_t *setOf,
-                                                  const uint32_t *v1Of, const uint32_t *seq,
+                                                  const uint32_t *v1Of, const uint32_t *sc,
                                                   uint32_t cnt, uint32_t *retry) {
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;
@@ -249,7 +253,7 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
             shared_acquire();                                       // row loads complete before the re-read
             uint32_t v2[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v2[u] = ld_agent(seq + setOf[ent[u]]);
+            for (int u = 0; u < U; ++u) v2[u] = ld_agent(sc + 2ull * setOf[ent[u]]);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 // One verdict per row: every lane of the row's group must have seen the unchanged
@@ -423,7 +427,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                                                            __HIP_MEMORY_SCOPE_AGENT);
                         break;
                     }
-                    const uint32_t v1 = pending ? ld_agent(tb.seq + set) : 0u;
+                    const uint32_t v1 = pending ? ld_agent(seq_of(tb, set)) : 0u;
                     const bool busy = pending && (v1 & 1u);          // a writer holds the set: look again later
                     shared_acquire();                                // the word is read before any key or row
                     const int w = probe_wave<W, KPW, true>(tb.K, key, set, pending && !busy);
@@ -440,7 +444,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                     wave_lds_fence();
                     if (fmask)
                         copy_rows_checked<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], &s_set[wave][0],
-                                             &s_v1[wave][0], tb.seq, (uint32_t)__popcll(fmask), &s_retry[wave][0]);
+                                             &s_v1[wave][0], tb.sc, (uint32_t)__popcll(fmask), &s_retry[wave][0]);
                     wave_lds_fence();
                     bool again = false;
                     if (found) {
@@ -740,8 +744,13 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
                     pending = false;
                 }
             }
-            uint32_t old = 1u;
-            if (pending) old = __hip_atomic_fetch_or(tb.seq + set, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // one 64-bit atomic on the set's {seq, ctr} word: takes the set and reads its counter
+            uint64_t word = 1ull;
+            if (pending)
+                word = __hip_atomic_fetch_or(reinterpret_cast<uint64_t *>(seq_of(tb, set)), 1ull, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t old = (uint32_t)word;
+            const uint32_t c = (uint32_t)(word >> 32);
             const bool own = pending && !(old & 1u);
             if (!__ballot(own)) {
                 __builtin_amdgcn_s_sleep(8);
@@ -749,7 +758,6 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
             }
             shared_acquire();                                        // the word is owned before the set is read
             int way = probe_wave<W, KPW, true>(tb.K, key, set, own);
-            const uint32_t c = own ? ld_agent(tb.ctr + set) : 0u;
             bool fresh = own && way < 0;
             if (tb.T) {                                              // LRU policy (Alg. 3)
                 if (fresh) {
@@ -771,7 +779,6 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
             }
             const uint64_t freshmask = __ballot(fresh);
             if (fresh) {
-                st_agent(tb.ctr + set, c + 1u);
                 st_agent(tb.K + (uint64_t)set * W + (uint32_t)way, key);
                 const int r = rank_in(freshmask);
                 s_dst[wave][r] = (uint64_t)set * W + (uint32_t)way;
@@ -785,7 +792,9 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
             }
             shared_release();                                        // rows and keys land before the words move on
             if (own) {
-                st_agent(tb.seq + set, fresh ? old + 2u : old);
+                // let go: a changed set gets seq + 2 and ctr + 1 in one store, an unchanged one its old word
+                st_agent(reinterpret_cast<uint64_t *>(seq_of(tb, set)),
+                         fresh ? (((uint64_t)(c + 1u) << 32) | (uint64_t)(old + 2u)) : word);
                 pending = false;
             }
         }
@@ -844,7 +853,7 @@ __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
             const uint64_t gmask = pendmask & lt_end & ~(le_leader >> 1);    // lanes leader .. end-1 that are pending
             const bool is_leader = pending && lane == leader;
 
-            uint32_t v = is_leader ? ld_agent(tb.seq + set) : 0u;
+            uint32_t v = is_leader ? ld_agent(seq_of(tb, set)) : 0u;
             v = (uint32_t)__shfl((int)v, leader, kWave);
             const bool busy = pending && (v & 1u);
             shared_acquire();                                        // the word is read before the keys
@@ -865,7 +874,7 @@ __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
             bool won = false;
             if (is_leader && !busy && group_needs) {
                 uint32_t expect = v;
-                won = __hip_atomic_compare_exchange_strong(tb.seq + set, &expect, v + 1u, __ATOMIC_RELAXED,
+                won = __hip_atomic_compare_exchange_strong(seq_of(tb, set), &expect, v + 1u, __ATOMIC_RELAXED,
                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             const bool gwon = __shfl((int)won, leader, kWave) != 0;
@@ -883,7 +892,7 @@ __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
                                     (uint32_t)__popcll(actmask));
                 wave_lds_fence();
                 shared_release();                                    // rows land before the word moves on
-                if (won) st_agent(tb.seq + set, v + 2u);
+                if (won) st_agent(seq_of(tb, set), v + 2u);
                 if (act) pending = false;
             }
         }
@@ -898,10 +907,19 @@ __global__ void fill_keys_kernel(int64_t *K, uint64_t n, int64_t v) {
         K[i] = v;
 }
 
-__global__ void fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v) {
-    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+// Export / import of the victim counters: ctr[s] <-> the upper half of the set's {seq, ctr} word.
+// An import leaves every sequence word at zero (no writer, nothing in flight).
+__global__ void counters_out_kernel(const uint32_t *sc, uint64_t S, uint32_t *ctr) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < S;
          i += (uint64_t)gridDim.x * blockDim.x)
-        p[i] = v;
+        ctr[i] = sc[2 * i + 1];
+}
+__global__ void counters_in_kernel(uint32_t *sc, uint64_t S, const uint32_t *ctr) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < S;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        sc[2 * i] = 0u;
+        sc[2 * i + 1] = ctr[i];
+    }
 }
 
 // Dump (Sec. 4.2): compact the non-empty keys of a slot range.  A work-group takes a tile of
@@ -1027,8 +1045,7 @@ struct hps_cache {
     uint32_t W, d;
     int64_t  *K;
     float    *V;
-    uint32_t *ctr;
-    uint32_t *seq;
+    uint32_t *sc;                         // [S][2]: {sequence word, victim counter}
     uint64_t *ring;                       // 2 * kRing counter words, all zero between calls
     std::mutex word_mu;
     std::unordered_map<void *, uint32_t> word_of_stream;
@@ -1058,8 +1075,7 @@ Table table_of(const hps_cache *c) {
     Table t;
     t.K = c->K;
     t.V = c->V;
-    t.ctr = c->ctr;
-    t.seq = c->seq;
+    t.sc = c->sc;
     t.S = (uint32_t)c->S;
     t.smask = (c->S & (c->S - 1)) == 0 ? (uint32_t)(c->S - 1) : 0u;
     if (c->S == 1) t.smask = 0;           // S = 1: "h % 1" = 0 (a zero mask means "use modulo")
@@ -1226,7 +1242,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->S = capacity / ways;
     c->W = ways;
     c->d = dim;
-    c->K = nullptr; c->V = nullptr; c->ctr = nullptr; c->seq = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr; c->word_half = 0;
+    c->K = nullptr; c->V = nullptr; c->sc = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr; c->word_half = 0;
     c->policy = policy;
     c->g.store(0);
     c->concurrent_writers.store(1);
@@ -1238,8 +1254,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     if (e == hipSuccess && c->n_cus <= 0) c->n_cus = 256;
     if (e == hipSuccess) e = hipMalloc(&c->K, capacity * sizeof(int64_t));
     if (e == hipSuccess) e = hipMalloc(&c->V, capacity * (size_t)dim * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&c->ctr, c->S * sizeof(uint32_t));
-    if (e == hipSuccess) e = hipMalloc(&c->seq, c->S * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(&c->sc, c->S * 2 * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->ring, 2 * kRing * sizeof(uint64_t));
     if (e == hipSuccess) e = hipMalloc(&c->flags, sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemsetAsync(c->flags, 0, sizeof(uint32_t), 0);
@@ -1252,8 +1267,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipMemsetAsync(c->V, 0, capacity * (size_t)dim * sizeof(float), 0);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ctr, 0, c->S * sizeof(uint32_t), 0);
-    if (e == hipSuccess) e = hipMemsetAsync(c->seq, 0, c->S * sizeof(uint32_t), 0);
+    if (e == hipSuccess) e = hipMemsetAsync(c->sc, 0, c->S * 2 * sizeof(uint32_t), 0);
     if (e == hipSuccess) e = hipMemsetAsync(c->ring, 0, 2 * kRing * sizeof(uint64_t), 0);
     if (e == hipSuccess) e = hipStreamSynchronize(0);
     if (e != hipSuccess) {
@@ -1262,8 +1276,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
         (void)hipGetLastError();
         if (c->K) (void)hipFree(c->K);
         if (c->V) (void)hipFree(c->V);
-        if (c->ctr) (void)hipFree(c->ctr);
-        if (c->seq) (void)hipFree(c->seq);
+        if (c->sc) (void)hipFree(c->sc);
         if (c->ring) (void)hipFree(c->ring);
         if (c->T) (void)hipFree(c->T);
         if (c->flags) (void)hipFree(c->flags);
@@ -1280,8 +1293,7 @@ hps_status_t hps_cache_destroy(hps_cache_t *c) {
     hipError_t e = hipSuccess, e2;
     if ((e2 = hipFree(c->K)) != hipSuccess) e = e2;
     if ((e2 = hipFree(c->V)) != hipSuccess) e = e2;
-    if ((e2 = hipFree(c->ctr)) != hipSuccess) e = e2;
-    if ((e2 = hipFree(c->seq)) != hipSuccess) e = e2;
+    if ((e2 = hipFree(c->sc)) != hipSuccess) e = e2;
     if ((e2 = hipFree(c->ring)) != hipSuccess) e = e2;
     if (c->T && (e2 = hipFree(c->T)) != hipSuccess) e = e2;
     if ((e2 = hipFree(c->flags)) != hipSuccess) e = e2;
@@ -1315,7 +1327,7 @@ hps_status_t hps_cache_flags(hps_cache_t *c, uint32_t *flags, int clear) {
 hps_status_t hps_cache_debug_set_seq(hps_cache_t *c, uint64_t set, uint32_t value) {
     if (hps_status_t s = check_handle(c)) return s;
     if (set >= c->S) return fail(HPS_ERR_INVALID_ARG, "set index out of range");
-    HIP_TRY(hipMemcpy(c->seq + set, &value, sizeof(uint32_t), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->sc + 2 * set, &value, sizeof(uint32_t), hipMemcpyHostToDevice));
     return HPS_OK;
 }
 
@@ -1429,7 +1441,8 @@ hps_status_t hps_cache_export(hps_cache_t *c, int64_t *keys, uint32_t *ctr, floa
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t slots = c->S * c->W;
     HIP_TRY(hipMemcpyAsync(keys, c->K, slots * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
-    HIP_TRY(hipMemcpyAsync(ctr, c->ctr, c->S * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(counters_out_kernel, dim3(1024), dim3(256), 0, st, c->sc, (uint64_t)c->S, ctr);
+    HIP_TRY(hipGetLastError());
     if (vals)
         HIP_TRY(hipMemcpyAsync(vals, c->V, slots * c->d * sizeof(float), hipMemcpyDeviceToDevice, st));
     return HPS_OK;
@@ -1442,10 +1455,9 @@ hps_status_t hps_cache_import(hps_cache_t *c, const int64_t *keys, const uint32_
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t slots = c->S * c->W;
     HIP_TRY(hipMemcpyAsync(c->K, keys, slots * sizeof(int64_t), hipMemcpyDeviceToDevice, st));
-    HIP_TRY(hipMemcpyAsync(c->ctr, ctr, c->S * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
     if (vals)
         HIP_TRY(hipMemcpyAsync(c->V, vals, slots * c->d * sizeof(float), hipMemcpyDeviceToDevice, st));
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, c->seq, (uint64_t)c->S, 0u);
+    hipLaunchKernelGGL(counters_in_kernel, dim3(1024), dim3(256), 0, st, c->sc, (uint64_t)c->S, ctr);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
