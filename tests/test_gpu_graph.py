@@ -8,7 +8,8 @@ import torch
 from oracle import OracleCache
 from paper_2210_08804_amd import binding as B
 from paper_2210_08804_amd import inputs
-from harness import DeviceCache, SENTINEL
+from harness import (DeviceCache, SENTINEL, assert_same_state, check_state_invariants,
+                     insert_is_order_independent)
 
 pytestmark = pytest.mark.gpu
 
@@ -70,3 +71,66 @@ def test_graph_replays_match_eager_results(checked):
             exp = np.full((512, d), SENTINEL, dtype=np.uint32)
             _, omi, _ = oc.query(ids[:512], exp)
             assert (gmi == omi).all() and (got == exp).all() and len(omi) < 100
+
+
+def test_dedup_query_fill_insert_expand_as_one_graph():
+    """Sec. 2.2 + Alg. 1 without a host round trip, captured once and replayed on new key batches:
+    dedup -> query of the distinct keys (count read on the device) -> fetch of the missing distinct
+    rows -> insert of them -> expansion to the positions.  Every replay is checked against the
+    same steps on the oracle; the cache warms up from replay to replay."""
+    import oracle
+    S, W, d, n = 1 << 12, 8, 32, 6000
+    with DeviceCache(S * W, W, d, concurrent_writers=False) as gc:
+        oc = OracleCache(S * W, W, d)
+        dd = B.hps_dedup_create(n)
+        try:
+            dk = torch.zeros(n, dtype=torch.int64, device="cuda")
+            uk = torch.empty(n, dtype=torch.int64, device="cuda")
+            inv = torch.empty(n, dtype=torch.int32, device="cuda")
+            nu = torch.zeros(1, dtype=torch.int32, device="cuda")
+            urows = torch.empty(n, d, dtype=torch.float32, device="cuda")
+            mrows = torch.empty(n, d, dtype=torch.float32, device="cuda")
+            mi = torch.empty(n, dtype=torch.int32, device="cuda")
+            mk = torch.empty(n, dtype=torch.int64, device="cuda")
+            nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+            out = torch.empty(n, d, dtype=torch.float32, device="cuda")
+            g = torch.cuda.CUDAGraph()
+            cs = torch.cuda.Stream()
+            cs.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(cs):
+                g.capture_begin()
+                B.hps_dedup(dd, dk, n, uk, inv, nu, cs)
+                B.hps_cache_query_dn(gc.h, uk, n, nu, urows, mi, mk, nm, cs)
+                B.hps_backing_fetch(mk, n, d, version=0, rows=mrows, n_dev=nm, scatter_idx=mi, scatter_out=urows, stream=cs)
+                B.hps_cache_insert_dn(gc.h, mk, mrows, n, nm, cs)
+                B.hps_expand_rows(urows, inv, n, d, out, cs)
+                g.capture_end()
+            torch.cuda.synchronize()
+            misses = []
+            for replay in range(5):
+                keys = inputs.zipf_keys(n, 20000, 1.1, 70 + replay)
+                dk.copy_(torch.from_numpy(keys))
+                out.view(torch.int32).fill_(SENTINEL)
+                urows.view(torch.int32).fill_(SENTINEL)
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                ou, _ = oracle.dedup(keys)
+                _, omi, omk = oc.query(ou, np.zeros((len(ou), d), dtype=np.uint32))
+                assert int(nu.item()) == len(ou) and int(nm.item()) == len(omi)
+                assert sorted(mk[:len(omi)].cpu().tolist()) == sorted(omk.tolist())
+                assert (out.view(torch.int32).cpu().numpy().view(np.uint32)
+                        == inputs.backing_rows(keys, d).view(np.uint32)).all()
+                exact = insert_is_order_independent(oc, omk)
+                oc.insert(omk, inputs.backing_rows(omk, d).view(np.uint32))
+                state = gc.export()
+                if exact:
+                    assert_same_state(state, oc)
+                else:
+                    check_state_invariants(*state, oc.set_of)
+                oc.load_state(*state)
+                misses.append(len(omi))
+            assert misses[-1] < misses[0]
+        finally:
+            torch.cuda.synchronize()
+            B.hps_dedup_destroy(dd)
