@@ -26,5 +26,21 @@ def build(extra=()):
     return LIB
 
 
+C_DEMO_SRC = os.path.join(ROOT, "tests", "c_abi_demo.c")
+C_DEMO_LIB = os.path.join(ROOT, "tests", "libhps_c_demo.so")
+
+
+def build_c_demo():
+    """The plain-C caller of the library that one GPU test runs (gcc, C99, no C++ anywhere)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-pedantic", "-fPIC", "-shared",
+           "-I", os.path.join(ROOT, "include"), "-isystem", os.path.join(rocm, "include"), C_DEMO_SRC, "-o", C_DEMO_LIB,
+           "-L", HERE, "-l:libhps_cache.so", "-Wl,-rpath,$ORIGIN/../paper_2210_08804_amd",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64"]
+    subprocess.run(cmd, check=True)
+    return C_DEMO_LIB
+
+
 if __name__ == "__main__":
     print(build(sys.argv[1:]))
+    print(build_c_demo())
