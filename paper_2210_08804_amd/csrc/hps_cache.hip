@@ -809,7 +809,7 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
 // Two lanes of a group that found the same slot (a key given twice) are thinned to one per round.
 // Lanes of different groups that meet on a set compete by compare-and-swap on its word; no lane
 // waits while its wave owns a set.
-template <int W>
+template <int W, int KPW>
 __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
     __shared__ uint64_t s_dst[kWavesPerWg][kWave];
     __shared__ uint32_t s_srcrow[kWavesPerWg][kWave];
@@ -823,15 +823,16 @@ __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
         const uint32_t nd = *a.n_dev;
         n = nd < n ? nd : n;
     }
-    const uint32_t n_tiles = (n + kWave - 1) / kWave;
+    const uint32_t n_tiles = (n + KPW - 1) / KPW;
     const uint32_t wave_global = blockIdx.x * kWavesPerWg + wave;
     const uint32_t n_waves = gridDim.x * kWavesPerWg;
     const uint64_t le_lane = lane == 63 ? ~0ull : ((2ull << lane) - 1);     // bits 0..lane
 
     for (uint32_t tile = wave_global; tile < n_tiles; tile += n_waves) {
-        const uint32_t i = tile * kWave + lane;
-        const int64_t key = i < n ? a.keys[i] : kEmpty;
-        bool pending = i < n && !is_reserved(key);
+        const uint32_t i = tile * KPW + lane;
+        const bool mine = lane < KPW && i < n;
+        const int64_t key = mine ? a.keys[i] : kEmpty;
+        bool pending = mine && !is_reserved(key);
         const uint32_t set = pending ? set_of(key, tb.S, tb.smask) : 0u;
 
         uint32_t rounds = 0;
@@ -1177,8 +1178,9 @@ hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, 
     a.g = make_geom(c->d);
     // insert: 16 keys per wave while 64 would leave fewer than 8 waves per CU
     // insert: 16 keys per wave (measured best from 1 K to 1 M keys: 8, 32 and 64 are 3-45 % slower)
-    // update: 64 keys per wave (16 and 32 measured 10 % slower on 2^18 rows, 9-55 % on a 40 GB refresh)
-    const uint32_t kpw = kInsert ? (uint32_t)kInsertKpw : (uint32_t)kWave;
+    // update: 64 keys per wave, 16 for batches below 32,768 keys (measured: 8,192 rows 16 us instead
+    // of 23 us, equal at 45,056, 8-18 % slower from 65,536 rows up and 9-55 % on a 40 GB refresh)
+    const uint32_t kpw = kInsert ? (uint32_t)kInsertKpw : (n < 32768 ? 16u : (uint32_t)kWave);
     const uint64_t tiles = (n + kpw - 1) / kpw;
     uint64_t blocks = (tiles + kWavesPerWg - 1) / kWavesPerWg;
     if (blocks > (1u << 16)) blocks = 1u << 16;
@@ -1187,7 +1189,8 @@ hps_status_t launch_write(hps_cache *c, const int64_t *keys, const float *vals, 
 #define HPS_CASE(w)                                                                         \
     case w:                                                                                 \
         if (kInsert) hipLaunchKernelGGL((insert_kernel<w, kInsertKpw>), grid, block, 0, st, a); \
-        else hipLaunchKernelGGL((update_kernel<w>), grid, block, 0, st, a);                 \
+        else if (kpw == 16) hipLaunchKernelGGL((update_kernel<w, 16>), grid, block, 0, st, a);  \
+        else hipLaunchKernelGGL((update_kernel<w, 64>), grid, block, 0, st, a);                 \
         break;
         HPS_CASE(1) HPS_CASE(2) HPS_CASE(4) HPS_CASE(8) HPS_CASE(16) HPS_CASE(32) HPS_CASE(64)
 #undef HPS_CASE
