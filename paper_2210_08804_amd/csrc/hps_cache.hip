@@ -924,63 +924,72 @@ __global__ void counters_in_kernel(uint32_t *sc, uint64_t S, const uint32_t *ctr
 }
 
 // Dump (Sec. 4.2): compact the non-empty keys of a slot range.  A work-group takes a tile of
-// 256*KPT slots, keeps KPT keys per lane in registers, and needs one counter atomic per tile
-// (same counter-word scheme as query).  Inside a tile the slots are visited set-major
-// (q -> set q mod SPT, way q div SPT, SPT = sets per tile), so keys of one set end up SPT
-// entries apart in the output instead of next to each other.
+// 256*KPT consecutive slots, keeps KPT keys per lane in registers, and needs one counter atomic
+// per tile (same counter-word scheme as query).  The output keeps slot order inside a tile, so the
+// keys of one set stay next to each other: an Update over the dumped keys then takes each set once
+// for all its keys (update_kernel groups such runs) and writes the rows of a set, which are
+// contiguous in memory, together.
 template <int KPT>
 __global__ void __launch_bounds__(kBlock) dump_kernel(const int64_t *__restrict__ K, uint64_t first,
-                                                      uint64_t n_slots, uint32_t W, int64_t *keys_out,
+                                                      uint64_t n_slots, int64_t *keys_out,
                                                       uint32_t *n_out, uint64_t *slot,
                                                       uint32_t n_tiles) {
     constexpr uint32_t kTileSlots = kBlock * KPT;
-    static_assert(KPT * kWavesPerWg <= kWave, "the count scan runs in one wave");
-    __shared__ uint32_t s_cnt[KPT * kWavesPerWg];          // [j][wave] counts, then exclusive prefixes
+    constexpr int kCnt = KPT * kWavesPerWg;                // one count per (j, wave)
+    static_assert(kCnt <= kBlock, "the count scan gives every count its own thread");
+    __shared__ uint32_t s_cnt[kCnt];                       // [j][wave] counts, then exclusive prefixes
+    __shared__ uint32_t s_wtot[kWavesPerWg];
     __shared__ uint32_t s_base;
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
-    const uint32_t spt = kTileSlots / W;                  // W <= 64 divides 256*KPT
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         int64_t key[KPT];
-        uint32_t rank[KPT];
 #pragma unroll
         for (int j = 0; j < KPT; ++j) {
             const uint32_t q = (uint32_t)j * kBlock + threadIdx.x;
-            const uint64_t i = (uint64_t)tile * kTileSlots + (uint64_t)(q % spt) * W + q / spt;
+            const uint64_t i = (uint64_t)tile * kTileSlots + q;
             key[j] = i < n_slots ? K[first + i] : kEmpty;
         }
 #pragma unroll
         for (int j = 0; j < KPT; ++j) {
             const uint64_t m = __ballot(key[j] != kEmpty);
-            rank[j] = (uint32_t)rank_in(m);
             if (lane == 0) s_cnt[j * kWavesPerWg + wave] = (uint32_t)__popcll(m);
         }
         __syncthreads();
-        if (wave == 0) {                                   // exclusive scan of the KPT*4 (<= 64) counts
-            const uint32_t c = lane < KPT * kWavesPerWg ? s_cnt[lane] : 0u;
-            uint32_t incl = c;
+        // exclusive scan of the kCnt counts over the work-group: inside each wave, then across waves
+        const uint32_t c = threadIdx.x < (uint32_t)kCnt ? s_cnt[threadIdx.x] : 0u;
+        uint32_t incl = c;
 #pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const uint32_t up = (uint32_t)__shfl_up((int)incl, o, kWave);
-                if (lane >= o) incl += up;
-            }
-            if (lane < KPT * kWavesPerWg) s_cnt[lane] = incl - c;
-            const uint32_t total = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
-            if (lane == 0) {
-                const uint64_t old = __hip_atomic_fetch_add(slot, (1ull << 32) | (uint64_t)total,
-                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_base = (uint32_t)old;
-                if ((uint32_t)(old >> 32) + 1u == n_tiles) {
-                    *n_out = (uint32_t)old + total;
-                    __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t up = (uint32_t)__shfl_up((int)incl, o, kWave);
+            if (lane >= o) incl += up;
+        }
+        if (lane == kWave - 1) s_wtot[wave] = incl;
+        __syncthreads();
+        uint32_t woff = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerWg; ++w) {
+            const uint32_t t = s_wtot[w];
+            if (w < wave) woff += t;
+            total += t;
+        }
+        if (threadIdx.x < (uint32_t)kCnt) s_cnt[threadIdx.x] = woff + incl - c;
+        if (threadIdx.x == 0) {
+            const uint64_t old = __hip_atomic_fetch_add(slot, (1ull << 32) | (uint64_t)total,
+                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_base = (uint32_t)old;
+            if ((uint32_t)(old >> 32) + 1u == n_tiles) {
+                *n_out = (uint32_t)old + total;
+                __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();
         const uint32_t base = s_base;
 #pragma unroll
-        for (int j = 0; j < KPT; ++j)
-            if (key[j] != kEmpty) keys_out[base + s_cnt[j * kWavesPerWg + wave] + rank[j]] = key[j];
+        for (int j = 0; j < KPT; ++j) {
+            const uint64_t m = __ballot(key[j] != kEmpty);
+            if (key[j] != kEmpty) keys_out[base + s_cnt[j * kWavesPerWg + wave] + (uint32_t)rank_in(m)] = key[j];
+        }
         __syncthreads();
     }
 }
@@ -1498,12 +1507,12 @@ hps_status_t hps_cache_dump(hps_cache_t *c, size_t first_slot, size_t n_slots, i
     if (n_slots >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n_slots must be < 2^32 per call");
     if (!n_out || (n_slots > 0 && !keys_out)) return fail(HPS_ERR_INVALID_ARG, "output pointer is NULL");
     if (!aligned(keys_out, 8) || !aligned(n_out, 4)) return fail(HPS_ERR_INVALID_ARG, "misaligned output buffer");
-    constexpr int kDumpKpt = 16;                       // 4096 slots per tile
+    constexpr int kDumpKpt = 32;                       // 8192 slots per tile (16 and 64 dump 15-20 % slower)
     uint32_t n_tiles = (uint32_t)((n_slots + kBlock * kDumpKpt - 1) / (kBlock * kDumpKpt));
     if (n_tiles == 0) n_tiles = 1;
     const uint32_t grid = n_tiles < (1u << 20) ? n_tiles : (1u << 20);
     hipLaunchKernelGGL((dump_kernel<kDumpKpt>), dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), c->K,
-                       (uint64_t)first_slot, (uint64_t)n_slots, c->W, keys_out, n_out, counter_word(c, stream), n_tiles);
+                       (uint64_t)first_slot, (uint64_t)n_slots, keys_out, n_out, counter_word(c, stream), n_tiles);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
