@@ -119,7 +119,8 @@ def refresh(a, np, torch, B):
     upd_ms, dump_ms = float(np.median(t_upd)), float(np.median(t_dump))
     cap_gb = m * 4 * d / 1e9
     paper = PAPER_REFRESH.get(int(round(a.capacity_gb))) if abs(a.capacity_gb - round(a.capacity_gb)) < 1e-6 else None
-    alg = m * (8 + 64 + 4 * d + 4 * d + 8)                 # key, key line, row in, row out, sequence word
+    # per row: key, row in, row out; per set (the dumped keys of a set are adjacent and share them): key line, sequence word
+    alg = m * (8 + 4 * d + 4 * d) + S * (8 * W + 8)
     res = {
         "metric": "cache refresh GB/s (cached bytes / Update time, dim 128 fp32)", "value": round(cap_gb / (upd_ms * 1e-3), 1),
         "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(upd_ms + dump_ms, 4),
