@@ -132,6 +132,52 @@ def test_insert_overlapping_queries_keeps_rows_whole():
                                expect_row=lambda k: [inputs.backing_rows(np.array([k]), d, 0).view(np.uint32)[0]])
 
 
+def test_inserts_and_updates_on_three_streams_keep_the_invariants():
+    """insert || insert || update across streams (batches that share keys, sets that fill up and
+    evict): after every round the state must be a legal cache state - no key twice, every key in
+    its own set, ways filled in order, counters equal to the number of keys each set took in, and
+    every row whole: the inserted row of its key or one of the rows an update gave it."""
+    from harness import check_state_invariants
+    S, W, d, n_i, n_u = 1 << 9, 8, 64, 3000, 2048
+    space = 3 * S * W
+    rng = np.random.Generator(np.random.PCG64(123))
+    oc = OracleCache(S * W, W, d)                        # only for set_of
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        sa, sb, su = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        versions = {}                                    # key -> versions an update carried for it
+        prev_ctr = np.zeros(S, dtype=np.int64)
+        for rnd in range(1, 9):
+            ka = rng.integers(0, space, n_i).astype(np.int64)
+            kb = np.concatenate([ka[: n_i // 2], rng.integers(0, space, n_i // 2).astype(np.int64)])   # half shared with ka
+            rng.shuffle(kb)
+            ku = rng.integers(0, space, n_u).astype(np.int64)
+            for k in ku.tolist():
+                versions.setdefault(k, set()).add(rnd)
+            da, db, du = (torch.from_numpy(k).cuda() for k in (ka, kb, ku))
+            ra = torch.from_numpy(inputs.backing_rows(ka, d, 0)).cuda()
+            rb = torch.from_numpy(inputs.backing_rows(kb, d, 0)).cuda()
+            ru = torch.from_numpy(inputs.backing_rows(ku, d, rnd)).cuda()
+            torch.cuda.synchronize()
+            B.hps_cache_insert(gc.h, da, ra, n_i, sa)
+            B.hps_cache_insert(gc.h, db, rb, n_i, sb)
+            B.hps_cache_update(gc.h, du, ru, n_u, su)
+            torch.cuda.synchronize()
+            gk, gctr, gv = gc.export()
+
+            def allowed(k):
+                vs = [0] + sorted(versions.get(k, ()))
+                return [inputs.backing_rows(np.array([k]), d, v).view(np.uint32)[0] for v in vs]
+            check_state_invariants(gk, gctr, gv, oc.set_of, expect_row=allowed)
+            # a set's counter grows by the number of keys it took in: never backwards, and never by more
+            # than the keys offered (a key of both batches can go in twice when its set overflowed
+            # and evicted it in between)
+            ctr = gctr.astype(np.int64)
+            assert (ctr >= prev_ctr).all()
+            assert 0 < (ctr - prev_ctr).sum() <= 2 * n_i
+            prev_ctr = ctr
+        assert B.hps_cache_flags(gc.h) == 0
+
+
 def test_more_stream_handles_than_counter_words():
     """Every stream that queries gets a counter word of its own; a caller that goes through more
     stream handles than the pool has words must still get correct miss lists on all of them."""
