@@ -297,7 +297,7 @@ __device__ __forceinline__ void copy_rows_shared(const RowGeom g, const float *_
             for (int u = 0; u < U; ++u) {
                 const uint32_t e = e0 + u * rpi + sub;
                 ent[u] = e < cnt ? e : 0u;
-                buf[u] = *(reinterpret_cast<const uint64_t *>(src + (uint64_t)srcRow[ent[u]] * g.d) + chunk);
+                buf[u] = __builtin_nontemporal_load(reinterpret_cast<const uint64_t *>(src + (uint64_t)srcRow[ent[u]] * g.d) + chunk);
             }
         };
         auto store = [&](const uint64_t (&buf)[U], const uint32_t (&ent)[U]) {
@@ -948,7 +948,7 @@ __global__ void __launch_bounds__(kBlock) dump_kernel(const int64_t *__restrict_
         for (int j = 0; j < KPT; ++j) {
             const uint32_t q = (uint32_t)j * kBlock + threadIdx.x;
             const uint64_t i = (uint64_t)tile * kTileSlots + q;
-            key[j] = i < n_slots ? K[first + i] : kEmpty;
+            key[j] = i < n_slots ? __builtin_nontemporal_load(K + first + i) : kEmpty;     // read once
         }
 #pragma unroll
         for (int j = 0; j < KPT; ++j) {
@@ -988,7 +988,8 @@ __global__ void __launch_bounds__(kBlock) dump_kernel(const int64_t *__restrict_
 #pragma unroll
         for (int j = 0; j < KPT; ++j) {
             const uint64_t m = __ballot(key[j] != kEmpty);
-            if (key[j] != kEmpty) keys_out[base + s_cnt[j * kWavesPerWg + wave] + (uint32_t)rank_in(m)] = key[j];
+            if (key[j] != kEmpty)
+                __builtin_nontemporal_store(key[j], keys_out + base + s_cnt[j * kWavesPerWg + wave] + (uint32_t)rank_in(m));
         }
         __syncthreads();
     }
