@@ -344,6 +344,43 @@ def test_device_side_batch_length_variants():
         assert_same_state(gc.export(), oc)
 
 
+def test_batch_sizes_around_the_launch_shape_boundaries():
+    """The query's tiling follows the batch size (keys per wave, waves per work-group, rounds over
+    the CUs); sizes just below, at and above every switch must all give the oracle's answer."""
+    S, W, d = 1 << 12, 8, 4
+    sizes = [255, 256, 257, 1023, 1024, 1025, 4095, 4096, 4097, 16383, 16384, 16385, 32767, 32769,
+             65535, 65536, 65537, 106496, 131071, 131072, 131073, 262143, 262144, 262145, 300001]
+    with DeviceCache(S * W, W, d) as gc:
+        oc = OracleCache(S * W, W, d)
+        resident = np.unique(inputs.uniform_keys(24000, 60000, 51))
+        for ck in np.array_split(resident, 6):
+            insert_both(gc, oc, ck, rows_u32(ck, d))
+        keys = inputs.uniform_keys(max(sizes), 60000, 52)
+        for n in sizes:
+            m = compare_query(gc, oc, keys[:n])
+            assert 0 < m < n
+
+
+def test_write_batch_sizes_around_the_kernel_switches():
+    """Insert and update pick their keys-per-wave from the batch size; sizes around a wave's key
+    count and around the update kernel's switch must leave the oracle's state."""
+    S, W, d = 1 << 14, 8, 4
+    with DeviceCache(S * W, W, d) as gc:
+        oc = OracleCache(S * W, W, d)
+        pool = np.unique(inputs.uniform_keys(90000, 1 << 40, 61))
+        rng = np.random.Generator(np.random.PCG64(62))
+        version = 0
+        for n in [1, 15, 16, 17, 63, 64, 65, 4095, 4097, 32767, 32768, 32769, 50000]:
+            version += 1
+            ins = rng.choice(pool, n, replace=False)
+            insert_both(gc, oc, ins, rows_u32(ins, d, 0))
+            upd = rng.choice(pool, n, replace=False)             # some cached, some not
+            gc.update(upd, rows_u32(upd, d, version))
+            oc.update(upd, rows_u32(upd, d, version))
+            assert_same_state(gc.export(), oc)
+        compare_query(gc, oc, pool[:50000])
+
+
 def test_query_with_device_side_batch_length():
     """hps_cache_query_dn looks up min(n_max, *n_dev) positions; the rest of the buffers is
     neither read as keys, nor written, nor reported."""
