@@ -1,14 +1,17 @@
 // Deduplication operator Q* = dedup(Q) of the paper's Sec. 2.2 and the row expansion that
 // follows the lookup of Q*, for gfx950.
 //
-// dedup is a hash join of the batch with itself in three launches:
-//   clear    the session's open-addressing table (one 8-byte key word per slot, 2n..4n slots);
+// dedup is a hash join of the batch with itself in two launches over an open-addressing table
+// (one 8-byte key word per slot, 2n..4n slots).  A session has two tables: a call works on the
+// clean one, and its second launch wipes the part of the other one that the previous call used,
+// so no call waits for a clear.
 //   insert   a work-group takes 1024 keys, elects one lane per distinct key of the tile in an
 //            LDS table (so a hot key reaches the global table once per tile, not once per
 //            occurrence), the elected lanes claim a slot of the global table with a 64-bit
 //            compare-and-swap, the lanes whose swap succeeded are numbered (one global counter
 //            atomic per tile) and write their key to unique_keys and their number beside the slot;
-//   inverse  every position finds its key's slot again and reads the number.
+//   inverse  every position finds its key's slot again and reads the number; the same launch
+//            clears the other table for the next call.
 // The order of unique_keys is the order in which tiles reach the counter: unspecified.
 #include <hip/hip_runtime.h>
 
@@ -58,6 +61,7 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
 
 // The table has slots 0..mask for ordinary keys and slot mask + 1 for the key whose value is the
 // free-slot marker itself.
+// (used once per table, when the session is created)
 __global__ void dedup_clear_kernel(int64_t *tkey, uint64_t n_slots, uint32_t *counter) {
     const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
     for (uint64_t i = t; i < n_slots; i += (uint64_t)gridDim.x * blockDim.x) tkey[i] = kEmpty;
@@ -142,10 +146,16 @@ __global__ void __launch_bounds__(kBlock) dedup_inverse_kernel(const int64_t *__
                                                                const int64_t *__restrict__ tkey,
                                                                const uint32_t *__restrict__ tuid, uint32_t mask,
                                                                const uint32_t *__restrict__ counter,
-                                                               uint32_t *inverse, uint32_t *n_unique) {
+                                                               uint32_t *inverse, uint32_t *n_unique,
+                                                               int64_t *other_tkey, uint64_t other_dirty,
+                                                               uint32_t *other_counter) {
     const uint64_t t = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
-    if (t == 0) *n_unique = *counter;
-    for (uint64_t i = t; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    if (t == 0) {
+        *n_unique = *counter;
+        *other_counter = 0u;
+    }
+    for (uint64_t i = t; i < n; i += stride) {
         const int64_t key = keys[i];
         uint32_t gs = mask + 1u;
         if (key != kEmpty) {
@@ -154,6 +164,8 @@ __global__ void __launch_bounds__(kBlock) dedup_inverse_kernel(const int64_t *__
         }
         inverse[i] = tuid[gs];
     }
+    // the slots the previous call used in the other table
+    for (uint64_t i = t; i < other_dirty; i += stride) other_tkey[i] = kEmpty;
 }
 
 // out[i] = rows[inverse[i]].  LPR lanes move one row, 16 bytes per lane; four rows per lane group
@@ -196,9 +208,12 @@ struct hps_dedup_session {
     int       device;
     size_t    max_n;
     uint64_t  slots;        // power of two >= 2 * max_n (>= 1024); one more slot follows them
-    int64_t  *tkey;         // [slots + 1]
-    uint32_t *tuid;         // [slots + 1]
-    uint32_t *counter;
+    int64_t  *tkey[3];      // [slots + 1] each; a call works on tkey[cur] (0 or 1), which is all free;
+                            // table 2 serves calls that are being captured into a graph (see hps_dedup)
+    uint32_t *tuid[3];      // [slots + 1] each
+    uint32_t *counter;      // one word per table (zero for the table in turn) and a spare one
+    uint64_t  dirty[2];     // leading slots of each table that a call has written and nobody cleared yet
+    int       cur;
     int       n_cus;
 };
 
@@ -233,19 +248,30 @@ hps_status_t hps_dedup_create(size_t max_n, hps_dedup_t **out) {
     s->magic = 0;
     s->max_n = max_n;
     s->slots = pow2_at_least(2 * (uint64_t)max_n);
-    s->tkey = nullptr;
-    s->tuid = nullptr;
+    s->tkey[0] = s->tkey[1] = s->tkey[2] = nullptr;
+    s->tuid[0] = s->tuid[1] = s->tuid[2] = nullptr;
     s->counter = nullptr;
+    s->dirty[0] = s->dirty[1] = 0;
+    s->cur = 0;
     s->n_cus = 256;
     hipError_t e = hipGetDevice(&s->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&s->n_cus, hipDeviceAttributeMultiprocessorCount, s->device);
     if (e == hipSuccess && s->n_cus <= 0) s->n_cus = 256;
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s->tkey), (s->slots + 1) * sizeof(int64_t));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s->tuid), (s->slots + 1) * sizeof(uint32_t));
+    for (int t = 0; t < 3; ++t) {
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s->tkey[t]), (s->slots + 1) * sizeof(int64_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s->tuid[t]), (s->slots + 1) * sizeof(uint32_t));
+    }
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&s->counter), 256);
+    for (int t = 0; t < 3 && e == hipSuccess; ++t) {
+        hipLaunchKernelGGL(dedup_clear_kernel, dim3(4096), dim3(kBlock), 0, 0, s->tkey[t], s->slots + 1, s->counter + t);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(0);
     if (e != hipSuccess) {
-        (void)hipFree(s->tkey);
-        (void)hipFree(s->tuid);
+        for (int t = 0; t < 3; ++t) {
+            (void)hipFree(s->tkey[t]);
+            (void)hipFree(s->tuid[t]);
+        }
         (void)hipFree(s->counter);
         delete s;
         (void)hipGetLastError();
@@ -264,8 +290,10 @@ hps_status_t hps_dedup_destroy(hps_dedup_t *s) {
     HIP_TRY(hipGetDevice(&prev));
     HIP_TRY(hipSetDevice(s->device));
     hipError_t e = hipDeviceSynchronize();
-    (void)hipFree(s->tkey);
-    (void)hipFree(s->tuid);
+    for (int t = 0; t < 3; ++t) {
+        (void)hipFree(s->tkey[t]);
+        (void)hipFree(s->tuid[t]);
+    }
     (void)hipFree(s->counter);
     s->magic = 0;
     delete s;
@@ -291,16 +319,37 @@ hps_status_t hps_dedup(hps_dedup_t *s, const int64_t *keys, size_t n, int64_t *u
     const uint64_t slots = pow2_at_least(2 * (uint64_t)n);            // <= s->slots because n <= max_n
     const uint32_t mask = (uint32_t)(slots - 1);
     const uint32_t cap = (uint32_t)s->n_cus * 8u;
-    uint64_t cb = (slots + 1 + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(dedup_clear_kernel, dim3((uint32_t)(cb < cap ? cb : cap)), dim3(kBlock), 0, q,
-                       s->tkey, slots + 1, s->counter);
     const uint64_t tiles = (n + kTile - 1) / kTile;
+    // A call that is being captured into a graph must be complete in itself, because the graph may
+    // be replayed any number of times between other calls: it clears its own table (the third
+    // one, which no other call touches) first and leaves the two alternating tables alone.
+    hipStreamCaptureStatus cap_status = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(q, &cap_status));
+    if (cap_status != hipStreamCaptureStatusNone) {
+        const uint64_t cb = (slots + 1 + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(dedup_clear_kernel, dim3((uint32_t)(cb < cap ? cb : cap)), dim3(kBlock), 0, q,
+                           s->tkey[2], slots + 1, s->counter + 2);
+        hipLaunchKernelGGL(dedup_insert_kernel, dim3((uint32_t)(tiles < cap ? tiles : cap)), dim3(kTile), 0, q,
+                           keys, (uint32_t)n, s->tkey[2], s->tuid[2], mask, s->counter + 2, unique_keys);
+        const uint64_t ib2 = (n + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(dedup_inverse_kernel, dim3((uint32_t)(ib2 < 4 * cap ? ib2 : 4 * cap)), dim3(kBlock), 0, q,
+                           keys, (uint32_t)n, s->tkey[2], s->tuid[2], mask, s->counter + 2, inverse, n_unique,
+                           s->tkey[2], (uint64_t)0, s->counter + 3);
+        HIP_TRY(hipGetLastError());
+        return HPS_OK;
+    }
+    const int t = s->cur, o = 1 - t;
     hipLaunchKernelGGL(dedup_insert_kernel, dim3((uint32_t)(tiles < cap ? tiles : cap)), dim3(kTile), 0, q,
-                       keys, (uint32_t)n, s->tkey, s->tuid, mask, s->counter, unique_keys);
-    const uint64_t ib = (n + kBlock - 1) / kBlock;
+                       keys, (uint32_t)n, s->tkey[t], s->tuid[t], mask, s->counter + t, unique_keys);
+    const uint64_t work = n > s->dirty[o] ? n : s->dirty[o];
+    const uint64_t ib = (work + kBlock - 1) / kBlock;
     hipLaunchKernelGGL(dedup_inverse_kernel, dim3((uint32_t)(ib < 4 * cap ? ib : 4 * cap)), dim3(kBlock), 0, q,
-                       keys, (uint32_t)n, s->tkey, s->tuid, mask, s->counter, inverse, n_unique);
+                       keys, (uint32_t)n, s->tkey[t], s->tuid[t], mask, s->counter + t, inverse, n_unique,
+                       s->tkey[o], s->dirty[o], s->counter + o);
     HIP_TRY(hipGetLastError());
+    s->dirty[t] = slots + 1;          // this call's slots, the extra one included
+    s->dirty[o] = 0;
+    s->cur = o;
     return HPS_OK;
 }
 
