@@ -2,6 +2,8 @@
 must see, for every hit, the complete row of ONE version of its key, never a mixture, and on one
 stream later queries never see an older version than earlier ones.  After both streams are
 synchronised a full re-query must equal the oracle (last version) bit for bit."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -12,6 +14,10 @@ from paper_2210_08804_amd import inputs
 from harness import DeviceCache, SENTINEL
 
 pytestmark = pytest.mark.gpu
+
+# HPS_TEST_SEED_SHIFT=k in the environment runs the same tests on other random streams (a longer
+# soak is then a shell loop over k); the default is the fixed stream the suite is tuned to.
+SEED_SHIFT = int(os.environ.get("HPS_TEST_SEED_SHIFT", "0"))
 
 
 def versions_seen(out_u32, keys, d, n_versions):
@@ -30,7 +36,7 @@ def versions_seen(out_u32, keys, d, n_versions):
 def test_update_overlapping_queries_never_tears_rows(S, W, d, n_q, n_u):
     n_versions, n_queries = 8, 24
     ids = np.arange(S * W // 2, dtype=np.int64)                         # about half full
-    rng = np.random.Generator(np.random.PCG64(S + d))
+    rng = np.random.Generator(np.random.PCG64(S + d + SEED_SHIFT))
     with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
         oc = OracleCache(S * W, W, d)
         for ck in np.array_split(ids, 16):
@@ -95,7 +101,7 @@ def test_insert_overlapping_queries_keeps_rows_whole():
     """Queries racing with inserts (cache filling up and evicting): every row returned is the
     complete row of its key (rows are a function of the key here), misses leave `out` untouched."""
     S, W, d, n_q, n_i = 1 << 9, 8, 128, 20000, 4096
-    rng = np.random.Generator(np.random.PCG64(99))
+    rng = np.random.Generator(np.random.PCG64(99 + SEED_SHIFT))
     with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
         qs, ws = torch.cuda.Stream(), torch.cuda.Stream()
         ins_keys = [rng.integers(0, 3 * S * W, n_i).astype(np.int64) for _ in range(12)]
@@ -140,7 +146,7 @@ def test_inserts_and_updates_on_three_streams_keep_the_invariants():
     from harness import check_state_invariants
     S, W, d, n_i, n_u = 1 << 9, 8, 64, 3000, 2048
     space = 3 * S * W
-    rng = np.random.Generator(np.random.PCG64(123))
+    rng = np.random.Generator(np.random.PCG64(123 + SEED_SHIFT))
     oc = OracleCache(S * W, W, d)                        # only for set_of
     with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
         sa, sb, su = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
