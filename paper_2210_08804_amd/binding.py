@@ -1,4 +1,4 @@
-"""Thin ctypes binding of include/hps_cache.h: argument marshalling only.
+"""Thin ctypes binding of include/hps_cache.h, hps_lookup.h and hps_dedup.h: argument marshalling only.
 
 Every function has the name of the C entry point it calls.  Tensors are torch CUDA (ROCm)
 tensors used purely as device buffers; `stream` is a torch.cuda.Stream or None (= the current
