@@ -1,5 +1,6 @@
 """Seeded generators: determinism, ranges, and the backing-row formula against big integers."""
 import numpy as np
+import pytest
 
 from paper_2210_08804_amd import inputs
 
@@ -62,3 +63,32 @@ def test_vocab_sizes_log_uniform():
     v = inputs.log_uniform_vocab(26, 1e3, 1e8, 7)
     assert v.shape == (26,) and v.min() >= 1000 and v.max() <= 10 ** 8
     assert (v == inputs.log_uniform_vocab(26, 1e3, 1e8, 7)).all()
+
+
+@pytest.mark.parametrize("alpha,space", [(1.05, 10 ** 8), (1.2, 10 ** 6), (1.5, 10 ** 5)])
+def test_zipf_keys_follow_the_power_law(alpha, space):
+    """The key streams stand in for the paper's power-law query distributions (Sec. 2.2; its
+    synthetic dataset draws with alpha = 1.2 and sends about 95 % of the lookups to 10 % of the
+    table, Sec. 7.1).  Checked against the closed form of the sampled law: the share of lookups
+    that fall on the hottest fraction f of the key space is ((f N)^(1-alpha) - 1) / (N^(1-alpha) - 1),
+    and the rank-frequency curve has slope -alpha in log-log."""
+    n = 400000
+    keys = inputs.zipf_keys(n, space, alpha, 11)
+    a = 1.0 - alpha
+    for f in (0.001, 0.01, 0.1, 0.5):
+        share = float((keys < f * space).mean())
+        expect = ((f * space) ** a - 1.0) / (float(space) ** a - 1.0)
+        assert abs(share - expect) < 0.004, (f, share, expect)
+    if alpha == 1.2:
+        assert 0.94 < float((keys < 0.1 * space).mean()) < 0.975        # the paper's "95 % on 10 %"
+    # slope of log(count) over log(rank) for the ranks that occur often enough to be measured
+    counts = np.bincount(keys[keys < 200], minlength=200).astype(np.float64)
+    ranks = np.arange(1, 201, dtype=np.float64)
+    ok = counts >= 50
+    # the sampled law is the continuous density integrated over [r, r+1): compare with that
+    expect = (ranks + 1.0) ** a - ranks ** a
+    expect = expect / expect[ok].sum() * counts[ok].sum()
+    rel = np.abs(counts[ok] - expect[ok]) / np.sqrt(expect[ok])
+    assert rel.max() < 6.0, "rank frequencies leave the power law by more than sampling noise"
+    slope = np.polyfit(np.log(ranks[ok][2:]), np.log(counts[ok][2:]), 1)[0]
+    assert abs(slope + alpha) < 0.15, slope
