@@ -8,6 +8,8 @@ batch, or new keys overwriting keys of the same batch) are checked by the invari
 every insert the oracle adopts the GPU's way placement, because the order in which the new keys
 of one batch take their ways is free and decides which of them is evicted first later on.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -19,6 +21,9 @@ from harness import (DeviceCache, EMPTY_KEY, RESERVED_KEY, SENTINEL, assert_same
                      check_state_invariants, insert_is_order_independent)
 
 pytestmark = pytest.mark.gpu
+
+# HPS_TEST_SEED_SHIFT=k runs the randomised sequence test on another random stream (for soak runs)
+SEED_SHIFT = int(os.environ.get("HPS_TEST_SEED_SHIFT", "0"))
 
 
 @pytest.fixture(autouse=True, params=["checked", "plain", "dedup"])
@@ -456,7 +461,7 @@ def test_query_multi_matches_per_table_oracles():
 
 def test_random_op_sequences_against_oracle():
     S, W, d = 300, 8, 16
-    rng = np.random.Generator(np.random.PCG64(77))
+    rng = np.random.Generator(np.random.PCG64(77 + SEED_SHIFT))
     with DeviceCache(S * W, W, d) as gc:
         oc = OracleCache(S * W, W, d)
         ver = 0
