@@ -28,7 +28,7 @@ METRIC = "cache query Mkeys/s + achieved HBM GB/s (dim 128 fp32, Zipf keys)"
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--workload", choices=["query", "refresh", "stream", "multi", "concurrent", "dedup", "write"], default="query",
+    p.add_argument("--workload", choices=["query", "refresh", "stream", "multi", "concurrent", "dedup", "write", "lookup"], default="query",
                    help="query: the headline hot-cache query (default); refresh: dump every cached key, then "
                         "update every cached row (the paper's Table 3); stream: query + miss fill + insert per "
                         "step on a cold cache; multi: 26 tables in one launch; concurrent: queries on one "
@@ -54,6 +54,7 @@ def parse():
     p.add_argument("--graph", type=int, default=0, help="1: replay the timed launches from one HIP graph")
     p.add_argument("--streams", type=int, default=3,
                    help="also time the same batches issued round-robin over this many streams (0: skip)")
+    p.add_argument("--threshold", type=float, default=0.8, help="lookup: hit-rate threshold t of Alg. 1")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-batches", type=int, default=100)
     p.add_argument("--calibrate-copy", action="store_true",
@@ -294,6 +295,66 @@ def write_batches(a, np, torch, B, inputs):
     print(json.dumps(res))
 
 
+def lookup_alg1(a, np, torch, B, inputs):
+    """Algorithm 1 end to end: hps_lookup on a cold cache with the library's host map as the lower
+    tier (2^22 keys x dim fp32 in host memory), cache = 5 % of the key space, batches of
+    1024 x 26 Zipf(1.2) keys (the paper's serving batch, Sec. 7.2).  A step is one hps_lookup call,
+    timed on the host (the call returns when `out` is complete); the background insertions of the
+    asynchronous mode overlap later calls."""
+    import time as _time
+    d, W = a.dim, a.ways
+    space = 1 << 22
+    S = (space // 20) // W
+    n = 1024 * a.features
+    steps = min(a.steps, 300)
+    hm = B.hps_hostmap_create(d, 16, space)
+    chunk = 1 << 19
+    ids = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    rows = torch.empty(chunk, d, dtype=torch.float32, device="cuda")
+    for lo in range(0, space, chunk):                     # rows generated on the device, stored on the host
+        ids.copy_(torch.arange(lo, lo + chunk, dtype=torch.int64, device="cuda"))
+        B.hps_backing_fetch(ids, chunk, d, version=0, rows=rows)
+        B.hps_hostmap_put(hm, ids.cpu().numpy(), rows.cpu().numpy())
+    del ids, rows
+    h = (B.hps_cache_create(S * W, W, d) if a.policy == "counter"
+         else B.hps_cache_create_policy(S * W, W, d, B.HPS_POLICY_LRU))
+    fetch = B.hps_hostmap_fetch_fn()
+    lk = B.hps_lookup_create(h, n, a.threshold, np.zeros(d, np.float32), fetch, user=hm)
+    keys = [torch.from_numpy(inputs.zipf_keys(n, space, 1.2, s + 1)).cuda() for s in range(steps)]
+    out = torch.empty(n, d, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    lat, rate, mode = [], [], []
+    for s in range(steps):
+        t0 = _time.perf_counter()
+        r, sync = B.hps_lookup(lk, keys[s], n, out)
+        torch.cuda.synchronize()
+        lat.append((_time.perf_counter() - t0) * 1e3)
+        rate.append(r)
+        mode.append(sync)
+    B.hps_lookup_drain(lk)
+    lat = np.array(lat)
+    tail = slice(steps // 2, steps)
+    first_async = next((i for i, m in enumerate(mode) if not m), None)
+    res = {"metric": "Alg. 1 lookup Mkeys/s (hps_lookup with a host-memory lower tier, stable stage)",
+           "value": round(n / (lat[tail].mean() * 1e-3) / 1e6, 1), "unit": "Mkeys/s", "n_gpus": 1, "steps": steps, "warmup": 0,
+           "ms_per_step": round(float(lat[tail].mean()), 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"hps_lookup: {n} Zipf(1.2) keys per call over {space} keys, cache {S} sets x {W} ways x dim {d} (5 % of the keys), "
+                                  f"threshold {a.threshold}, lower tier = host map", "replacement_policy": a.policy,
+                      "first_asynchronous_call": first_async,
+                      "hit_rate_every_25_calls": [round(float(x), 3) for x in rate[::25]],
+                      "latency_ms_first10": [round(float(x), 3) for x in lat[:10]],
+                      "latency_ms_stable": {"mean": round(float(lat[tail].mean()), 4), "p50": round(float(np.median(lat[tail])), 4),
+                                            "p99": round(float(np.percentile(lat[tail], 99)), 4)},
+                      "hit_rate_first10": [round(float(x), 4) for x in rate[:10]],
+                      "hit_rate_stable": round(float(np.mean(rate[steps // 2:])), 4)}}
+    B.hps_lookup_destroy(lk)
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    B.hps_hostmap_destroy(hm)
+    print(json.dumps(res))
+
+
 def multi_table(a, np, torch, B, inputs):
     """26 independent caches (vocabulary log-uniform in [1e3, 1e8], each cache 20 % of its vocabulary,
     at most 2^22 slots), one Zipf(1.05) key per table and sample, 131072 samples, one launch."""
@@ -425,6 +486,8 @@ def main():
         return dedup_lookup(a, np, torch, B, inputs)
     if a.workload == "write":
         return write_batches(a, np, torch, B, inputs)
+    if a.workload == "lookup":
+        return lookup_alg1(a, np, torch, B, inputs)
 
     S, W, d = 1 << a.log2_sets, a.ways, a.dim
     slots = S * W

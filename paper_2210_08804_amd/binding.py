@@ -31,6 +31,8 @@ EXPORTS = (
     "hps_cache_flags", "hps_cache_debug_set_seq", "hps_cache_query_dn",
     "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
     "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
+    "hps_hostmap_create", "hps_hostmap_destroy", "hps_hostmap_put", "hps_hostmap_get", "hps_hostmap_fetch",
+    "hps_hostmap_stats",
 )
 
 # lower-tier fetch callback of hps_lookup.h: (user, keys*, n, rows*)
@@ -77,6 +79,11 @@ def load_library():
         "hps_dedup_destroy": [vp],
         "hps_dedup": [vp, vp, sz, vp, vp, vp, vp],
         "hps_expand_rows": [vp, vp, sz, u32, vp, vp],
+        "hps_hostmap_create": [u32, u32, sz, C.POINTER(vp)],
+        "hps_hostmap_destroy": [vp],
+        "hps_hostmap_put": [vp, vp, vp, sz],
+        "hps_hostmap_get": [vp, vp, sz, vp, C.POINTER(sz)],
+        "hps_hostmap_stats": [vp, C.POINTER(sz), C.POINTER(sz)],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
         "hps_cache_insert": [vp, vp, vp, sz, vp],
@@ -97,6 +104,8 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = argtypes
+    lib.hps_hostmap_fetch.restype = None
+    lib.hps_hostmap_fetch.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -254,13 +263,14 @@ def hps_lookup_last_error() -> str:
     return load_library().hps_lookup_last_error().decode()
 
 
-def hps_lookup_create(cache, max_batch: int, hit_threshold: float, default_row, fetch) -> int:
+def hps_lookup_create(cache, max_batch: int, hit_threshold: float, default_row, fetch, user=None) -> int:
     """default_row: host float32 array of dim values; fetch: a FETCH_FN object, which the caller
-    must keep alive as long as the lookup object exists."""
+    must keep alive as long as the lookup object exists; user: the pointer handed to fetch
+    (for hps_hostmap_fetch_fn(): the host map)."""
     import numpy as np
     row = np.ascontiguousarray(default_row, dtype=np.float32)
     h = C.c_void_p()
-    _check_lookup(load_library().hps_lookup_create(cache, max_batch, hit_threshold, row.ctypes.data, fetch, None,
+    _check_lookup(load_library().hps_lookup_create(cache, max_batch, hit_threshold, row.ctypes.data, fetch, user,
                                                    C.byref(h)))
     return h.value
 
@@ -311,3 +321,61 @@ def hps_dedup(session, keys, n, unique_keys, inverse, n_unique, stream=None) -> 
 def hps_expand_rows(rows, inverse, n, dim, out, stream=None) -> None:
     _check_dedup(load_library().hps_expand_rows(
         _ptr(rows, torch.float32), _ptr(inverse, torch.int32), n, dim, _ptr(out, torch.float32), _stream(stream)))
+
+
+# ---- hps_hostmap.h: host-memory stand-in for the lower tiers behind Alg. 1 (host numpy arrays)
+
+def _check_hostmap(status, what):
+    if status != HPS_OK:
+        raise HpsError(status, what)
+
+
+def hps_hostmap_create(dim: int, partitions: int = 16, reserve: int = 0) -> int:
+    h = C.c_void_p()
+    _check_hostmap(load_library().hps_hostmap_create(dim, partitions, reserve, C.byref(h)), "hps_hostmap_create")
+    return h.value
+
+
+def hps_hostmap_destroy(m) -> None:
+    _check_hostmap(load_library().hps_hostmap_destroy(m), "hps_hostmap_destroy")
+
+
+def hps_hostmap_put(m, keys, rows) -> None:
+    """keys: host int64 numpy array [n]; rows: host float32 numpy array [n, dim] (C-contiguous)."""
+    import numpy as np
+    keys = np.ascontiguousarray(keys, dtype=np.int64)
+    rows = np.ascontiguousarray(rows, dtype=np.float32)
+    _check_hostmap(load_library().hps_hostmap_put(m, keys.ctypes.data, rows.ctypes.data, keys.shape[0]), "hps_hostmap_put")
+
+
+def hps_hostmap_get(m, keys, dim: int):
+    """Returns (rows [n, dim] float32, number of keys that were not stored)."""
+    import numpy as np
+    keys = np.ascontiguousarray(keys, dtype=np.int64)
+    rows = np.empty((keys.shape[0], dim), dtype=np.float32)
+    absent = C.c_size_t()
+    _check_hostmap(load_library().hps_hostmap_get(m, keys.ctypes.data, keys.shape[0], rows.ctypes.data, C.byref(absent)),
+                   "hps_hostmap_get")
+    return rows, absent.value
+
+
+def hps_hostmap_stats(m):
+    """Returns (keys stored, absent keys served so far)."""
+    nk, na = C.c_size_t(), C.c_size_t()
+    _check_hostmap(load_library().hps_hostmap_stats(m, C.byref(nk), C.byref(na)), "hps_hostmap_stats")
+    return nk.value, na.value
+
+
+def hps_hostmap_fetch_fn():
+    """The library's own hps_hostmap_fetch as a FETCH_FN, to pass to hps_lookup_create together
+    with user=<the host map>."""
+    return C.cast(load_library().hps_hostmap_fetch, FETCH_FN)
+
+
+def hps_hostmap_fetch(m, keys, dim: int):
+    """Calls the C entry point of that name (the hps_fetch_fn-shaped lookup) on host arrays."""
+    import numpy as np
+    keys = np.ascontiguousarray(keys, dtype=np.int64)
+    rows = np.empty((keys.shape[0], dim), dtype=np.float32)
+    load_library().hps_hostmap_fetch(m, keys.ctypes.data, keys.shape[0], rows.ctypes.data)
+    return rows

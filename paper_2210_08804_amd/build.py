@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRCS = [os.path.join(HERE, "csrc", f) for f in ("hps_cache.hip", "hps_lookup.hip", "hps_dedup.hip")]
+SRCS = [os.path.join(HERE, "csrc", f) for f in ("hps_cache.hip", "hps_lookup.hip", "hps_dedup.hip", "hps_hostmap.cpp")]
 LIB = os.path.join(HERE, "libhps_cache.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

@@ -1,0 +1,198 @@
+// Host-memory key -> row store: the stand-in for the lower tiers behind Algorithm 1 (Sec. 3.1,
+// Sec. 5 of the paper).  Plain C++: partitioned hash maps, rows in per-partition slabs.
+#include <atomic>
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "hps_hostmap.h"
+
+namespace {
+
+constexpr uint64_t kMagic = 0x4850534D41503031ull;
+constexpr size_t kSlabRows = 1 << 14;           // rows per allocation unit of a partition
+constexpr size_t kParallelFrom = 2048;          // batches at least this long are served by several threads
+
+uint64_t mix64(uint64_t x) {
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+struct Partition {
+    std::mutex mu;
+    std::unordered_map<int64_t, uint64_t> index;      // key -> row number in this partition
+    std::vector<float *> slabs;                       // kSlabRows rows each
+    uint64_t n_rows = 0;
+};
+
+}  // namespace
+
+struct hps_hostmap {
+    uint64_t magic;
+    uint32_t dim;
+    uint32_t n_part;
+    std::vector<Partition> parts;
+    std::atomic<size_t> n_absent_total;
+};
+
+namespace {
+
+inline uint32_t part_of(const hps_hostmap *m, int64_t key) {
+    return (uint32_t)(mix64((uint64_t)key) >> 40) & (m->n_part - 1);
+}
+
+float *row_ptr(const hps_hostmap *m, const Partition &p, uint64_t r) {
+    return p.slabs[r / kSlabRows] + (r % kSlabRows) * m->dim;
+}
+
+// Serve positions whose key lives in partitions [p0, p1): the positions of each partition are
+// gathered first so that its lock is taken once.
+size_t get_range(hps_hostmap *m, const int64_t *keys, size_t n, float *rows,
+                 const std::vector<uint32_t> &part, uint32_t p0, uint32_t p1) {
+    size_t absent = 0;
+    std::vector<size_t> mine;
+    for (uint32_t p = p0; p < p1; ++p) {
+        mine.clear();
+        for (size_t i = 0; i < n; ++i)
+            if (part[i] == p) mine.push_back(i);
+        if (mine.empty()) continue;
+        Partition &P = m->parts[p];
+        std::lock_guard<std::mutex> lk(P.mu);
+        for (size_t i : mine) {
+            auto it = P.index.find(keys[i]);
+            if (it == P.index.end()) {
+                std::memset(rows + i * m->dim, 0, sizeof(float) * m->dim);
+                ++absent;
+            } else {
+                std::memcpy(rows + i * m->dim, row_ptr(m, P, it->second), sizeof(float) * m->dim);
+            }
+        }
+    }
+    return absent;
+}
+
+}  // namespace
+
+extern "C" {
+
+hps_status_t hps_hostmap_create(uint32_t dim, uint32_t partitions, size_t reserve, hps_hostmap_t **out) {
+    if (!out) return HPS_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (dim == 0 || partitions == 0 || partitions > 256 || (partitions & (partitions - 1)) != 0)
+        return HPS_ERR_INVALID_ARG;
+    hps_hostmap *m = new (std::nothrow) hps_hostmap();
+    if (!m) return HPS_ERR_OOM;
+    try {
+        m->dim = dim;
+        m->n_part = partitions;
+        m->parts = std::vector<Partition>(partitions);
+        for (auto &p : m->parts) p.index.reserve(reserve / partitions + 16);
+    } catch (const std::bad_alloc &) {
+        delete m;
+        return HPS_ERR_OOM;
+    }
+    m->n_absent_total.store(0);
+    m->magic = kMagic;
+    *out = m;
+    return HPS_OK;
+}
+
+hps_status_t hps_hostmap_destroy(hps_hostmap_t *m) {
+    if (!m || m->magic != kMagic) return HPS_ERR_INVALID_ARG;
+    m->magic = 0;
+    for (auto &p : m->parts)
+        for (float *s : p.slabs) delete[] s;
+    delete m;
+    return HPS_OK;
+}
+
+hps_status_t hps_hostmap_put(hps_hostmap_t *m, const int64_t *keys, const float *rows, size_t n) {
+    if (!m || m->magic != kMagic) return HPS_ERR_INVALID_ARG;
+    if (n == 0) return HPS_OK;
+    if (!keys || !rows) return HPS_ERR_INVALID_ARG;
+    try {
+        for (size_t i = 0; i < n; ++i) {
+            Partition &P = m->parts[part_of(m, keys[i])];
+            std::lock_guard<std::mutex> lk(P.mu);
+            auto it = P.index.find(keys[i]);
+            uint64_t r;
+            if (it == P.index.end()) {
+                r = P.n_rows;
+                if (r / kSlabRows >= P.slabs.size()) P.slabs.push_back(new float[kSlabRows * (size_t)m->dim]);
+                P.index.emplace(keys[i], r);
+                ++P.n_rows;
+            } else {
+                r = it->second;
+            }
+            std::memcpy(row_ptr(m, P, r), rows + i * m->dim, sizeof(float) * m->dim);
+        }
+    } catch (const std::bad_alloc &) {
+        return HPS_ERR_OOM;
+    }
+    return HPS_OK;
+}
+
+hps_status_t hps_hostmap_get(hps_hostmap_t *m, const int64_t *keys, size_t n, float *rows, size_t *n_absent) {
+    if (!m || m->magic != kMagic) return HPS_ERR_INVALID_ARG;
+    if (n_absent) *n_absent = 0;
+    if (n == 0) return HPS_OK;
+    if (!keys || !rows) return HPS_ERR_INVALID_ARG;
+    size_t absent = 0;
+    try {
+        std::vector<uint32_t> part(n);
+        for (size_t i = 0; i < n; ++i) part[i] = part_of(m, keys[i]);
+        uint32_t n_thr = 1;
+        if (n >= kParallelFrom) {
+            n_thr = std::thread::hardware_concurrency();
+            if (n_thr > 8) n_thr = 8;
+            if (n_thr > m->n_part) n_thr = m->n_part;
+            if (n_thr == 0) n_thr = 1;
+        }
+        if (n_thr == 1) {
+            absent = get_range(m, keys, n, rows, part, 0, m->n_part);
+        } else {
+            std::vector<size_t> part_absent(n_thr, 0);
+            std::vector<std::thread> threads;
+            for (uint32_t t = 0; t < n_thr; ++t) {
+                const uint32_t p0 = (uint32_t)((uint64_t)m->n_part * t / n_thr);
+                const uint32_t p1 = (uint32_t)((uint64_t)m->n_part * (t + 1) / n_thr);
+                threads.emplace_back([&, t, p0, p1] { part_absent[t] = get_range(m, keys, n, rows, part, p0, p1); });
+            }
+            for (auto &th : threads) th.join();
+            for (size_t a : part_absent) absent += a;
+        }
+    } catch (const std::exception &) {
+        return HPS_ERR_OOM;
+    }
+    m->n_absent_total.fetch_add(absent);
+    if (n_absent) *n_absent = absent;
+    return HPS_OK;
+}
+
+void hps_hostmap_fetch(void *user, const int64_t *keys, size_t n, float *rows) {
+    (void)hps_hostmap_get(static_cast<hps_hostmap_t *>(user), keys, n, rows, nullptr);
+}
+
+hps_status_t hps_hostmap_stats(hps_hostmap_t *m, size_t *n_keys, size_t *n_absent_total) {
+    if (!m || m->magic != kMagic) return HPS_ERR_INVALID_ARG;
+    if (n_keys) {
+        size_t k = 0;
+        for (auto &p : m->parts) {
+            std::lock_guard<std::mutex> lk(p.mu);
+            k += p.index.size();
+        }
+        *n_keys = k;
+    }
+    if (n_absent_total) *n_absent_total = m->n_absent_total.load();
+    return HPS_OK;
+}
+
+}  // extern "C"

@@ -107,3 +107,45 @@ def test_lookup_argument_errors_and_empty_batch():
             assert rate == 1.0 and not sync
         finally:
             B.hps_lookup_destroy(lk)
+
+
+@pytest.mark.parametrize("threshold", [0.8, 2.0])
+def test_lookup_with_the_native_host_map_as_lower_tier(threshold):
+    """Alg. 1 end to end without Python in the loop: the lower tier is the library's host map
+    (hps_hostmap.h), handed to the lookup object as its fetch function."""
+    S, W, d, n, space = 1 << 10, 8, 32, 6000, 12000
+    default_row = np.full(d, 0.25, dtype=np.float32)
+    all_keys = np.arange(space, dtype=np.int64)
+    hm = B.hps_hostmap_create(d, 16, space)
+    B.hps_hostmap_put(hm, all_keys, inputs.backing_rows(all_keys, d, 0))
+    fetch = B.hps_hostmap_fetch_fn()
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        oc = OracleCache(S * W, W, d)
+        lk = B.hps_lookup_create(gc.h, n, threshold, default_row, fetch, user=hm)
+        try:
+            modes = []
+            for step in range(12):
+                keys = inputs.zipf_keys(n, space, 1.1, step + 1)
+                out = torch.zeros(n, d, dtype=torch.float32, device="cuda")
+                rate, sync = B.hps_lookup(lk, torch.from_numpy(keys).cuda(), n, out)
+                B.hps_lookup_drain(lk)
+                torch.cuda.synchronize()
+                exp_out, exp_rate, exp_sync, to_insert = reference_step(oc, keys, d, threshold, default_row)
+                assert np.float32(rate) == exp_rate and sync == exp_sync
+                assert (out.cpu().numpy().view(np.uint32) == exp_out).all()
+                modes.append(sync)
+                if to_insert is not None:
+                    exact = insert_is_order_independent(oc, to_insert)
+                    oc.insert(to_insert, inputs.backing_rows(to_insert, d, 0))
+                    state = gc.export()
+                    if exact:
+                        assert_same_state(state, oc)
+                    else:
+                        check_state_invariants(*state, oc.set_of)
+                    oc.load_state(*state)
+            assert modes[0] and (threshold > 1 or not modes[-1])
+            n_keys, n_absent = B.hps_hostmap_stats(hm)
+            assert n_keys == space and n_absent == 0          # every key asked for was a stored one
+        finally:
+            B.hps_lookup_destroy(lk)
+            B.hps_hostmap_destroy(hm)
