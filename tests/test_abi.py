@@ -82,7 +82,7 @@ def test_headers_are_plain_c(tmp_path):
     """The boundary is a C ABI: both headers must compile as C99 with no HIP or C++ in sight."""
     import subprocess
     src = tmp_path / "use.c"
-    src.write_text('#include "hps_lookup.h"\n#include "hps_dedup.h"\n#include "hps_cache.h"\n'
+    src.write_text('#include "hps_lookup.h"\n#include "hps_dedup.h"\n#include "hps_hostmap.h"\n#include "hps_cache.h"\n'
                    "int main(void) { hps_cache_t *c = 0; hps_lookup_t *l = 0; (void)c; (void)l; return HPS_OK; }\n")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                     "-I", os.path.join(ROOT, "include"), str(src)], check=True)
