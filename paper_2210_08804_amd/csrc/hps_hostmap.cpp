@@ -1,6 +1,7 @@
 // Host-memory key -> row store: the stand-in for the lower tiers behind Algorithm 1 (Sec. 3.1,
 // Sec. 5 of the paper).  Plain C++: partitioned hash maps, rows in per-partition slabs.
 #include <atomic>
+#include <condition_variable>
 #include <cstdint>
 #include <cstring>
 #include <mutex>
@@ -15,7 +16,7 @@ namespace {
 
 constexpr uint64_t kMagic = 0x4850534D41503031ull;
 constexpr size_t kSlabRows = 1 << 14;           // rows per allocation unit of a partition
-constexpr size_t kParallelFrom = 2048;          // batches at least this long are served by several threads
+constexpr size_t kParallelFrom = 1024;          // batches at least this long are served by the helper threads too
 
 uint64_t mix64(uint64_t x) {
     x ^= x >> 30;
@@ -35,12 +36,32 @@ struct Partition {
 
 }  // namespace
 
+// One batch lookup handed to the map's helper threads: thread t serves partitions
+// [n_part * t / n_thr, n_part * (t + 1) / n_thr).
+struct Job {
+    const int64_t *keys = nullptr;
+    size_t n = 0;
+    float *rows = nullptr;
+    const std::vector<uint32_t> *part = nullptr;
+    std::vector<size_t> absent;
+};
+
 struct hps_hostmap {
     uint64_t magic;
     uint32_t dim;
     uint32_t n_part;
     std::vector<Partition> parts;
     std::atomic<size_t> n_absent_total;
+    // helper threads (n_thr - 1 of them; the caller is thread 0), woken once per parallel lookup
+    uint32_t n_thr = 1;
+    std::vector<std::thread> helpers;
+    std::mutex job_mu;            // one parallel lookup at a time; a second caller serves itself alone
+    std::mutex pool_mu;
+    std::condition_variable pool_cv, done_cv;
+    uint64_t generation = 0;
+    uint32_t running = 0;
+    bool stop = false;
+    Job job;
 };
 
 namespace {
@@ -79,6 +100,25 @@ size_t get_range(hps_hostmap *m, const int64_t *keys, size_t n, float *rows,
     return absent;
 }
 
+void helper_main(hps_hostmap *m, uint32_t t) {
+    uint64_t seen = 0;
+    for (;;) {
+        {
+            std::unique_lock<std::mutex> lk(m->pool_mu);
+            m->pool_cv.wait(lk, [&] { return m->stop || m->generation != seen; });
+            if (m->stop) return;
+            seen = m->generation;
+        }
+        const uint32_t p0 = (uint32_t)((uint64_t)m->n_part * t / m->n_thr);
+        const uint32_t p1 = (uint32_t)((uint64_t)m->n_part * (t + 1) / m->n_thr);
+        m->job.absent[t] = get_range(m, m->job.keys, m->job.n, m->job.rows, *m->job.part, p0, p1);
+        {
+            std::lock_guard<std::mutex> lk(m->pool_mu);
+            if (--m->running == 0) m->done_cv.notify_one();
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -100,6 +140,17 @@ hps_status_t hps_hostmap_create(uint32_t dim, uint32_t partitions, size_t reserv
         return HPS_ERR_OOM;
     }
     m->n_absent_total.store(0);
+    uint32_t n_thr = std::thread::hardware_concurrency();
+    if (n_thr > 8) n_thr = 8;
+    if (n_thr > partitions) n_thr = partitions;
+    if (n_thr == 0) n_thr = 1;
+    m->n_thr = n_thr;
+    m->job.absent.assign(n_thr, 0);
+    try {
+        for (uint32_t t = 1; t < n_thr; ++t) m->helpers.emplace_back(helper_main, m, t);
+    } catch (const std::exception &) {                     // fewer helpers than planned: run with those
+        m->n_thr = (uint32_t)m->helpers.size() + 1;
+    }
     m->magic = kMagic;
     *out = m;
     return HPS_OK;
@@ -108,6 +159,12 @@ hps_status_t hps_hostmap_create(uint32_t dim, uint32_t partitions, size_t reserv
 hps_status_t hps_hostmap_destroy(hps_hostmap_t *m) {
     if (!m || m->magic != kMagic) return HPS_ERR_INVALID_ARG;
     m->magic = 0;
+    {
+        std::lock_guard<std::mutex> lk(m->pool_mu);
+        m->stop = true;
+    }
+    m->pool_cv.notify_all();
+    for (auto &th : m->helpers) th.join();
     for (auto &p : m->parts)
         for (float *s : p.slabs) delete[] s;
     delete m;
@@ -149,25 +206,27 @@ hps_status_t hps_hostmap_get(hps_hostmap_t *m, const int64_t *keys, size_t n, fl
     try {
         std::vector<uint32_t> part(n);
         for (size_t i = 0; i < n; ++i) part[i] = part_of(m, keys[i]);
-        uint32_t n_thr = 1;
-        if (n >= kParallelFrom) {
-            n_thr = std::thread::hardware_concurrency();
-            if (n_thr > 8) n_thr = 8;
-            if (n_thr > m->n_part) n_thr = m->n_part;
-            if (n_thr == 0) n_thr = 1;
-        }
-        if (n_thr == 1) {
-            absent = get_range(m, keys, n, rows, part, 0, m->n_part);
-        } else {
-            std::vector<size_t> part_absent(n_thr, 0);
-            std::vector<std::thread> threads;
-            for (uint32_t t = 0; t < n_thr; ++t) {
-                const uint32_t p0 = (uint32_t)((uint64_t)m->n_part * t / n_thr);
-                const uint32_t p1 = (uint32_t)((uint64_t)m->n_part * (t + 1) / n_thr);
-                threads.emplace_back([&, t, p0, p1] { part_absent[t] = get_range(m, keys, n, rows, part, p0, p1); });
+        std::unique_lock<std::mutex> pool(m->job_mu, std::defer_lock);
+        if (n >= kParallelFrom && m->n_thr > 1 && pool.try_lock()) {
+            m->job.keys = keys;
+            m->job.n = n;
+            m->job.rows = rows;
+            m->job.part = &part;
+            {
+                std::lock_guard<std::mutex> lk(m->pool_mu);
+                m->running = m->n_thr - 1;
+                ++m->generation;
             }
-            for (auto &th : threads) th.join();
-            for (size_t a : part_absent) absent += a;
+            m->pool_cv.notify_all();
+            const uint32_t p1 = (uint32_t)((uint64_t)m->n_part * 1 / m->n_thr);
+            absent = get_range(m, keys, n, rows, part, 0, p1);               // the caller is thread 0
+            {
+                std::unique_lock<std::mutex> lk(m->pool_mu);
+                m->done_cv.wait(lk, [&] { return m->running == 0; });
+            }
+            for (uint32_t t = 1; t < m->n_thr; ++t) absent += m->job.absent[t];
+        } else {
+            absent = get_range(m, keys, n, rows, part, 0, m->n_part);
         }
     } catch (const std::exception &) {
         return HPS_ERR_OOM;

@@ -64,7 +64,7 @@ struct hps_lookup_session {
     float    *h_rows;
     // background insertion
     hipStream_t side;
-    int64_t  *bg_d_ukeys;
+    int64_t  *bg_d_ukeys, *bg_h_keys;
     float    *bg_d_rows, *bg_h_rows;
     std::thread worker;
     std::mutex mu;
@@ -103,22 +103,43 @@ void launch_place(float *out, const uint32_t *idx, const uint32_t *src, const fl
 // Background thread: the asyncInsert procedure of Alg. 1 (lower-tier lookup, then insert).
 void worker_main(hps_lookup_session *L) {
     (void)hipSetDevice(L->device);
+    std::vector<Task> batch;
     for (;;) {
-        Task t;
+        batch.clear();
         {
             std::unique_lock<std::mutex> lk(L->mu);
             L->cv.wait(lk, [&] { return L->stop || !L->queue.empty(); });
             if (L->queue.empty()) return;                      // stop requested and nothing left
-            t = L->queue.front();
-            L->queue.pop_front();
+            // Everything that has queued up goes in one round (as long as it fits the buffers):
+            // when the lower tier is slower than the callers, the backlog stays bounded and keys
+            // that several queued batches ask for are fetched once.
+            size_t total = 0;
+            while (!L->queue.empty() && (batch.empty() || total + L->queue.front().m <= L->max_batch)) {
+                total += L->queue.front().m;
+                batch.push_back(L->queue.front());
+                L->queue.pop_front();
+            }
             L->busy = true;
         }
         std::string err;
-        hipError_t e = hipEventSynchronize(t.ready);
+        hipError_t e = hipSuccess;
+        for (const Task &t : batch)
+            if (e == hipSuccess) e = hipEventSynchronize(t.ready);
         if (e == hipSuccess) {
-            const uint32_t u = t.m;
-            L->fetch(L->user, t.h_keys, u, L->bg_h_rows);
-            e = hipMemcpyAsync(L->bg_d_ukeys, t.h_keys, (size_t)u * sizeof(int64_t), hipMemcpyHostToDevice, L->side);
+            const int64_t *ukeys = batch[0].h_keys;
+            uint32_t u = batch[0].m;
+            if (batch.size() > 1) {                            // merge, then make the keys distinct again
+                u = 0;
+                for (const Task &t : batch) {
+                    std::memcpy(L->bg_h_keys + u, t.h_keys, (size_t)t.m * sizeof(int64_t));
+                    u += t.m;
+                }
+                std::sort(L->bg_h_keys, L->bg_h_keys + u);
+                u = (uint32_t)(std::unique(L->bg_h_keys, L->bg_h_keys + u) - L->bg_h_keys);
+                ukeys = L->bg_h_keys;
+            }
+            L->fetch(L->user, ukeys, u, L->bg_h_rows);
+            e = hipMemcpyAsync(L->bg_d_ukeys, ukeys, (size_t)u * sizeof(int64_t), hipMemcpyHostToDevice, L->side);
             if (e == hipSuccess)
                 e = hipMemcpyAsync(L->bg_d_rows, L->bg_h_rows, (size_t)u * L->dim * sizeof(float),
                                    hipMemcpyHostToDevice, L->side);
@@ -127,10 +148,10 @@ void worker_main(hps_lookup_session *L) {
             if (e == hipSuccess) e = hipStreamSynchronize(L->side);
         }
         if (e != hipSuccess) err = std::string("background insertion: ") + hipGetErrorString(e);
-        (void)hipEventDestroy(t.ready);
+        for (const Task &t : batch) (void)hipEventDestroy(t.ready);
         {
             std::lock_guard<std::mutex> lk(L->mu);
-            L->free_key_bufs.push_back(t.h_keys);
+            for (const Task &t : batch) L->free_key_bufs.push_back(t.h_keys);
             if (!err.empty()) L->worker_error = err;
             L->busy = false;
         }
@@ -145,6 +166,7 @@ void free_all(hps_lookup_session *L) {
     (void)hipFree(L->bg_d_ukeys); (void)hipFree(L->bg_d_rows);
     (void)hipHostFree(L->h_n_miss); (void)hipHostFree(L->h_n_unique);
     (void)hipHostFree(L->h_ukeys); (void)hipHostFree(L->h_rows); (void)hipHostFree(L->bg_h_rows);
+    (void)hipHostFree(L->bg_h_keys);
     for (int64_t *p : L->free_key_bufs) (void)hipHostFree(p);
     if (L->side) (void)hipStreamDestroy(L->side);
 }
@@ -170,6 +192,7 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     L->d_miss_idx = L->d_n_miss = L->d_inv = L->d_n_unique = nullptr; L->d_miss_keys = L->d_ukeys = nullptr;
     L->d_rows = L->d_default = nullptr; L->h_n_miss = L->h_n_unique = nullptr; L->h_ukeys = nullptr;
     L->h_rows = nullptr; L->side = nullptr; L->bg_d_ukeys = nullptr; L->bg_d_rows = L->bg_h_rows = nullptr;
+    L->bg_h_keys = nullptr;
     const size_t nb = max_batch, rowb = (size_t)dim * sizeof(float);
     hipError_t e = hipGetDevice(&L->device);
     auto dev = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
@@ -180,6 +203,7 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     dev((void **)&L->d_default, rowb); dev((void **)&L->bg_d_ukeys, nb * 8); dev((void **)&L->bg_d_rows, nb * rowb);
     pin((void **)&L->h_n_miss, 4); pin((void **)&L->h_n_unique, 4);
     pin((void **)&L->h_ukeys, nb * 8); pin((void **)&L->h_rows, nb * rowb); pin((void **)&L->bg_h_rows, nb * rowb);
+    pin((void **)&L->bg_h_keys, nb * 8);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipMemcpy(L->d_default, default_row, rowb, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
