@@ -149,3 +149,41 @@ def test_lookup_with_the_native_host_map_as_lower_tier(threshold):
         finally:
             B.hps_lookup_destroy(lk)
             B.hps_hostmap_destroy(hm)
+
+
+def test_queued_background_batches_are_merged_and_stay_distinct():
+    """Asynchronous calls issued faster than the lower tier answers queue up; the worker merges
+    what has queued, the lower tier still sees distinct keys in every call, and once drained the
+    cache holds every key that was asked for."""
+    import time
+    S, W, d, n = 1 << 16, 8, 16, 5000                      # 27 k keys over 65 k sets: no set overflows
+    calls = []
+
+    def slow_fetch(user, keys_p, m, rows_p):
+        keys = np.ctypeslib.as_array(keys_p, shape=(m,)).copy()
+        calls.append(keys)
+        time.sleep(0.02)                                       # a slow tier: later batches pile up
+        rows = np.ctypeslib.as_array(rows_p, shape=(m, d))
+        rows[...] = inputs.backing_rows(keys, d, 0)
+
+    fetch = B.FETCH_FN(slow_fetch)
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        lk = B.hps_lookup_create(gc.h, 4 * n, 0.0, np.zeros(d, np.float32), fetch)
+        try:
+            asked = []
+            for step in range(8):
+                keys = inputs.uniform_keys(n, 40000, 80 + step)
+                asked.append(keys)
+                out = torch.zeros(n, d, dtype=torch.float32, device="cuda")
+                rate, sync = B.hps_lookup(lk, torch.from_numpy(keys).cuda(), n, out)
+                assert not sync
+            B.hps_lookup_drain(lk)
+            torch.cuda.synchronize()
+            assert all(len(np.unique(c)) == len(c) for c in calls), "the lower tier was handed a key twice in one call"
+            assert len(calls) < 8, "queued batches were not merged"
+            everything = np.unique(np.concatenate(asked))
+            got, mi, _ = gc.query(everything)
+            assert len(mi) == 0
+            assert (got == inputs.backing_rows(everything, d, 0).view(np.uint32)).all()
+        finally:
+            B.hps_lookup_destroy(lk)
