@@ -8,7 +8,8 @@
  * The lower storage tiers (Sec. 5) are the caller's: a fetch callback that receives the missing
  * keys in host memory and fills their rows in host memory.  Everything else runs on the device,
  * including the deduplication of the missing keys (Sec. 2.2, hps_dedup.h): only distinct keys
- * travel to the host.
+ * travel to the host.  In asynchronous mode that, too, happens on the background thread's
+ * stream: the call itself only copies the miss list aside.
  * One lookup object serves one stream of batches (it owns one workspace, the paper's `ws`); use
  * one object per concurrent inference worker, all on the same cache.
  */

@@ -38,9 +38,9 @@ __global__ void place_rows_kernel(float *out, const uint32_t *__restrict__ idx,
 }
 
 struct Task {                 // one queued asynchronous insertion
-    int64_t   *h_keys;        // pinned, the batch's distinct missing keys
+    int64_t   *d_keys;        // device copy of the batch's miss list (every occurrence)
     uint32_t   m;             // how many
-    hipEvent_t ready;         // the device-to-host copy of h_keys has finished
+    hipEvent_t ready;         // that copy has finished
 };
 
 }  // namespace
@@ -54,6 +54,7 @@ struct hps_lookup_session {
     hps_fetch_fn fetch;
     void        *user;
     hps_dedup_t *dd;          // dedup of the miss list before it leaves the device (Sec. 2.2)
+    hps_dedup_t *dd_bg;       // the same for the background thread (its calls run on the side stream)
     // workspace (the paper's ws): device side
     uint32_t *d_miss_idx, *d_n_miss, *d_inv, *d_n_unique;
     int64_t  *d_miss_keys, *d_ukeys;
@@ -64,7 +65,8 @@ struct hps_lookup_session {
     float    *h_rows;
     // background insertion
     hipStream_t side;
-    int64_t  *bg_d_ukeys, *bg_h_keys;
+    int64_t  *bg_d_ukeys, *bg_d_keys, *bg_h_keys;
+    uint32_t *bg_d_inv, *bg_d_n_unique, *bg_h_n_unique;
     float    *bg_d_rows, *bg_h_rows;
     std::thread worker;
     std::mutex mu;
@@ -123,26 +125,27 @@ void worker_main(hps_lookup_session *L) {
         }
         std::string err;
         hipError_t e = hipSuccess;
-        for (const Task &t : batch)
-            if (e == hipSuccess) e = hipEventSynchronize(t.ready);
-        if (e == hipSuccess) {
-            const int64_t *ukeys = batch[0].h_keys;
-            uint32_t u = batch[0].m;
-            if (batch.size() > 1) {                            // merge, then make the keys distinct again
-                u = 0;
-                for (const Task &t : batch) {
-                    std::memcpy(L->bg_h_keys + u, t.h_keys, (size_t)t.m * sizeof(int64_t));
-                    u += t.m;
-                }
-                std::sort(L->bg_h_keys, L->bg_h_keys + u);
-                u = (uint32_t)(std::unique(L->bg_h_keys, L->bg_h_keys + u) - L->bg_h_keys);
-                ukeys = L->bg_h_keys;
-            }
-            L->fetch(L->user, ukeys, u, L->bg_h_rows);
-            e = hipMemcpyAsync(L->bg_d_ukeys, ukeys, (size_t)u * sizeof(int64_t), hipMemcpyHostToDevice, L->side);
+        // the queued miss lists, one after the other in one device buffer, then made distinct
+        uint32_t total = 0;
+        for (const Task &t : batch) {
+            if (e == hipSuccess) e = hipStreamWaitEvent(L->side, t.ready, 0);
             if (e == hipSuccess)
-                e = hipMemcpyAsync(L->bg_d_rows, L->bg_h_rows, (size_t)u * L->dim * sizeof(float),
-                                   hipMemcpyHostToDevice, L->side);
+                e = hipMemcpyAsync(L->bg_d_keys + total, t.d_keys, (size_t)t.m * sizeof(int64_t),
+                                   hipMemcpyDeviceToDevice, L->side);
+            total += t.m;
+        }
+        if (e == hipSuccess &&
+            hps_dedup(L->dd_bg, L->bg_d_keys, total, L->bg_d_ukeys, L->bg_d_inv, L->bg_d_n_unique, L->side) != HPS_OK)
+            err = std::string("background dedup: ") + hps_dedup_last_error();
+        if (e == hipSuccess) e = hipMemcpyAsync(L->bg_h_n_unique, L->bg_d_n_unique, 4, hipMemcpyDeviceToHost, L->side);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(L->bg_h_keys, L->bg_d_ukeys, (size_t)total * sizeof(int64_t), hipMemcpyDeviceToHost, L->side);
+        if (e == hipSuccess) e = hipStreamSynchronize(L->side);
+        if (e == hipSuccess && err.empty()) {
+            const uint32_t u = *L->bg_h_n_unique;
+            L->fetch(L->user, L->bg_h_keys, u, L->bg_h_rows);
+            e = hipMemcpyAsync(L->bg_d_rows, L->bg_h_rows, (size_t)u * L->dim * sizeof(float),
+                               hipMemcpyHostToDevice, L->side);
             if (e == hipSuccess && hps_cache_insert(L->cache, L->bg_d_ukeys, L->bg_d_rows, u, L->side) != HPS_OK)
                 err = std::string("background insert: ") + hps_last_error();
             if (e == hipSuccess) e = hipStreamSynchronize(L->side);
@@ -151,7 +154,7 @@ void worker_main(hps_lookup_session *L) {
         for (const Task &t : batch) (void)hipEventDestroy(t.ready);
         {
             std::lock_guard<std::mutex> lk(L->mu);
-            for (const Task &t : batch) L->free_key_bufs.push_back(t.h_keys);
+            for (const Task &t : batch) L->free_key_bufs.push_back(t.d_keys);
             if (!err.empty()) L->worker_error = err;
             L->busy = false;
         }
@@ -161,13 +164,15 @@ void worker_main(hps_lookup_session *L) {
 
 void free_all(hps_lookup_session *L) {
     (void)hps_dedup_destroy(L->dd);
+    (void)hps_dedup_destroy(L->dd_bg);
     (void)hipFree(L->d_miss_idx); (void)hipFree(L->d_n_miss); (void)hipFree(L->d_inv); (void)hipFree(L->d_n_unique);
     (void)hipFree(L->d_miss_keys); (void)hipFree(L->d_ukeys); (void)hipFree(L->d_rows); (void)hipFree(L->d_default);
-    (void)hipFree(L->bg_d_ukeys); (void)hipFree(L->bg_d_rows);
+    (void)hipFree(L->bg_d_ukeys); (void)hipFree(L->bg_d_rows); (void)hipFree(L->bg_d_keys);
+    (void)hipFree(L->bg_d_inv); (void)hipFree(L->bg_d_n_unique); (void)hipHostFree(L->bg_h_n_unique);
     (void)hipHostFree(L->h_n_miss); (void)hipHostFree(L->h_n_unique);
     (void)hipHostFree(L->h_ukeys); (void)hipHostFree(L->h_rows); (void)hipHostFree(L->bg_h_rows);
     (void)hipHostFree(L->bg_h_keys);
-    for (int64_t *p : L->free_key_bufs) (void)hipHostFree(p);
+    for (int64_t *p : L->free_key_bufs) (void)hipFree(p);
     if (L->side) (void)hipStreamDestroy(L->side);
 }
 
@@ -188,11 +193,11 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     if (!L) return lfail(HPS_ERR_OOM, "host allocation failed");
     L->cache = cache; L->max_batch = max_batch; L->dim = dim; L->threshold = hit_threshold;
     L->fetch = fetch; L->user = user;
-    L->dd = nullptr;
+    L->dd = nullptr; L->dd_bg = nullptr;
     L->d_miss_idx = L->d_n_miss = L->d_inv = L->d_n_unique = nullptr; L->d_miss_keys = L->d_ukeys = nullptr;
     L->d_rows = L->d_default = nullptr; L->h_n_miss = L->h_n_unique = nullptr; L->h_ukeys = nullptr;
     L->h_rows = nullptr; L->side = nullptr; L->bg_d_ukeys = nullptr; L->bg_d_rows = L->bg_h_rows = nullptr;
-    L->bg_h_keys = nullptr;
+    L->bg_h_keys = nullptr; L->bg_d_keys = nullptr; L->bg_d_inv = L->bg_d_n_unique = L->bg_h_n_unique = nullptr;
     const size_t nb = max_batch, rowb = (size_t)dim * sizeof(float);
     hipError_t e = hipGetDevice(&L->device);
     auto dev = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
@@ -203,7 +208,8 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     dev((void **)&L->d_default, rowb); dev((void **)&L->bg_d_ukeys, nb * 8); dev((void **)&L->bg_d_rows, nb * rowb);
     pin((void **)&L->h_n_miss, 4); pin((void **)&L->h_n_unique, 4);
     pin((void **)&L->h_ukeys, nb * 8); pin((void **)&L->h_rows, nb * rowb); pin((void **)&L->bg_h_rows, nb * rowb);
-    pin((void **)&L->bg_h_keys, nb * 8);
+    pin((void **)&L->bg_h_keys, nb * 8); pin((void **)&L->bg_h_n_unique, 4);
+    dev((void **)&L->bg_d_keys, nb * 8); dev((void **)&L->bg_d_inv, nb * 4); dev((void **)&L->bg_d_n_unique, 4);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipMemcpy(L->d_default, default_row, rowb, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -214,7 +220,9 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
         delete L;
         return lfail(code, msg);
     }
-    if (const hps_status_t ds = hps_dedup_create(max_batch, &L->dd)) {
+    hps_status_t ds = hps_dedup_create(max_batch, &L->dd);
+    if (ds == HPS_OK) ds = hps_dedup_create(max_batch, &L->dd_bg);
+    if (ds != HPS_OK) {
         const std::string msg = std::string("hps_lookup_create: ") + hps_dedup_last_error();
         free_all(L);
         delete L;
@@ -276,26 +284,23 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     // asynchronous insertion: default vectors now, the real rows reach the cache later
     launch_place(out, L->d_miss_idx, nullptr, L->d_default, m, L->dim, st);
     LK_TRY(hipGetLastError());
-    if (hps_dedup(L->dd, L->d_miss_keys, m, L->d_ukeys, L->d_inv, L->d_n_unique, st) != HPS_OK)
-        return lfail(HPS_ERR_DEVICE, std::string("dedup: ") + hps_dedup_last_error());
+    // The miss list (every occurrence) is copied aside on the device and handed to the background
+    // thread, which deduplicates it on its own stream: this call does not wait for any of that.
     Task t;
     {
         std::lock_guard<std::mutex> lk(L->mu);
         if (!L->free_key_bufs.empty()) {
-            t.h_keys = L->free_key_bufs.back();
+            t.d_keys = L->free_key_bufs.back();
             L->free_key_bufs.pop_back();
         } else {
-            t.h_keys = nullptr;
+            t.d_keys = nullptr;
         }
     }
-    if (!t.h_keys) LK_TRY(hipHostMalloc((void **)&t.h_keys, L->max_batch * 8, hipHostMallocDefault));
+    if (!t.d_keys) LK_TRY(hipMalloc((void **)&t.d_keys, L->max_batch * 8));
+    t.m = m;
     LK_TRY(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
-    LK_TRY(hipMemcpyAsync(L->h_n_unique, L->d_n_unique, 4, hipMemcpyDeviceToHost, st));
-    LK_TRY(hipMemcpyAsync(t.h_keys, L->d_ukeys, (size_t)m * 8, hipMemcpyDeviceToHost, st));
+    LK_TRY(hipMemcpyAsync(t.d_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToDevice, st));
     LK_TRY(hipEventRecord(t.ready, st));
-    // the workspace is read by those copies; wait for them before the next call reuses it
-    LK_TRY(hipStreamSynchronize(st));
-    t.m = *L->h_n_unique;
     {
         std::lock_guard<std::mutex> lk(L->mu);
         L->queue.push_back(t);
