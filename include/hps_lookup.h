@@ -9,7 +9,9 @@
  * keys in host memory and fills their rows in host memory.  Everything else runs on the device,
  * including the deduplication of the missing keys (Sec. 2.2, hps_dedup.h): only distinct keys
  * travel to the host.  In asynchronous mode that, too, happens on the background thread's
- * stream: the call itself only copies the miss list aside.
+ * stream: the call itself only copies the miss list aside.  At most 64 such batches wait for the
+ * background thread; if the lower tier falls further behind, the oldest is dropped (its keys stay
+ * missing until a later batch asks for them again).
  * One lookup object serves one stream of batches (it owns one workspace, the paper's `ws`); use
  * one object per concurrent inference worker, all on the same cache.
  */

@@ -37,6 +37,10 @@ __global__ void place_rows_kernel(float *out, const uint32_t *__restrict__ idx,
     }
 }
 
+// Asynchronous insertions that may wait for the background thread.  Beyond that the oldest one is
+// dropped: cache insertion is best effort, its keys stay missing until a later batch asks again.
+constexpr size_t kMaxQueued = 64;
+
 struct Task {                 // one queued asynchronous insertion
     int64_t   *d_keys;        // device copy of the batch's miss list (every occurrence)
     uint32_t   m;             // how many
@@ -301,10 +305,19 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     LK_TRY(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
     LK_TRY(hipMemcpyAsync(t.d_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToDevice, st));
     LK_TRY(hipEventRecord(t.ready, st));
+    Task dropped;
+    bool drop = false;
     {
         std::lock_guard<std::mutex> lk(L->mu);
+        if (L->queue.size() >= kMaxQueued) {                  // the lower tier cannot keep up: the oldest batch goes
+            dropped = L->queue.front();
+            L->queue.pop_front();
+            L->free_key_bufs.push_back(dropped.d_keys);
+            drop = true;
+        }
         L->queue.push_back(t);
     }
+    if (drop) (void)hipEventDestroy(dropped.ready);
     L->cv.notify_one();
     return HPS_OK;
 }

@@ -187,3 +187,42 @@ def test_queued_background_batches_are_merged_and_stay_distinct():
             assert (got == inputs.backing_rows(everything, d, 0).view(np.uint32)).all()
         finally:
             B.hps_lookup_destroy(lk)
+
+
+def test_a_lower_tier_that_falls_far_behind_loses_the_oldest_batches_only():
+    """More asynchronous batches than may wait (64): the oldest are dropped, nothing breaks, and
+    what was not dropped arrives whole."""
+    import time
+    S, W, d, n, calls_n = 1 << 16, 8, 16, 500, 120
+    fetched = []
+
+    def slow_fetch(user, keys_p, m, rows_p):
+        keys = np.ctypeslib.as_array(keys_p, shape=(m,)).copy()
+        fetched.append(keys)
+        time.sleep(0.01)
+        np.ctypeslib.as_array(rows_p, shape=(m, d))[...] = inputs.backing_rows(keys, d, 0)
+
+    fetch = B.FETCH_FN(slow_fetch)
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        lk = B.hps_lookup_create(gc.h, n, 0.0, np.zeros(d, np.float32), fetch)      # one batch per background round
+        try:
+            asked = [np.arange(step * n, (step + 1) * n, dtype=np.int64) for step in range(calls_n)]
+            out = torch.zeros(n, d, dtype=torch.float32, device="cuda")
+            for keys in asked:
+                B.hps_lookup(lk, torch.from_numpy(keys).cuda(), n, out)
+            B.hps_lookup_drain(lk)
+            torch.cuda.synchronize()
+            got_keys = np.concatenate(fetched)
+            assert len(np.unique(got_keys)) == len(got_keys)
+            assert 64 * n <= len(got_keys) < calls_n * n, "either nothing was dropped or too much"
+            everything = np.concatenate(asked)
+            out_all, mi, mk = gc.query(everything)
+            assert sorted(mk.tolist()) == sorted(set(everything.tolist()) - set(got_keys.tolist()))
+            hit = np.ones(len(everything), dtype=bool)
+            hit[mi] = False
+            assert (out_all[hit] == inputs.backing_rows(everything[hit], d, 0).view(np.uint32)).all()
+            # the object still works
+            rate, sync = B.hps_lookup(lk, torch.from_numpy(asked[-1]).cuda(), n, out)
+            assert rate == 1.0 and not sync
+        finally:
+            B.hps_lookup_destroy(lk)
