@@ -28,7 +28,7 @@ METRIC = "cache query Mkeys/s + achieved HBM GB/s (dim 128 fp32, Zipf keys)"
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--workload", choices=["query", "refresh", "stream", "multi", "concurrent", "dedup", "write", "lookup"], default="query",
+    p.add_argument("--workload", choices=["query", "refresh", "refresh-host", "stream", "multi", "concurrent", "dedup", "write", "lookup"], default="query",
                    help="query: the headline hot-cache query (default); refresh: dump every cached key, then "
                         "update every cached row (the paper's Table 3); stream: query + miss fill + insert per "
                         "step on a cold cache; multi: 26 tables in one launch; concurrent: queries on one "
@@ -355,6 +355,49 @@ def lookup_alg1(a, np, torch, B, inputs):
     print(json.dumps(res))
 
 
+def refresh_from_host(a, np, torch, B, inputs):
+    """The whole refresh cycle of Sec. 6 with the lower tier in host memory (hps_cache_refresh):
+    dump, copy of the keys to the host, lookup in the host map, upload, Update, in batches of 2^18
+    slots, the host lookup of one batch overlapping the upload and Update of the previous one.
+    A step is one refresh of a full cache of 2^22 rows (2 GiB at dim 128)."""
+    import time as _time
+    d, W = a.dim, a.ways
+    n_keys = 1 << 22
+    S = n_keys // W
+    hm = B.hps_hostmap_create(d, 16, n_keys)
+    h = B.hps_cache_create(S * W, W, d)
+    chunk = 1 << 19
+    ids = torch.empty(chunk, dtype=torch.int64, device="cuda")
+    rows = torch.empty(chunk, d, dtype=torch.float32, device="cuda")
+    for lo in range(0, n_keys, chunk):
+        ids.copy_(torch.arange(lo, lo + chunk, dtype=torch.int64, device="cuda"))
+        B.hps_backing_fetch(ids, chunk, d, version=0, rows=rows)
+        B.hps_cache_insert(h, ids, rows, chunk)
+        B.hps_backing_fetch(ids, chunk, d, version=1, rows=rows)
+        B.hps_hostmap_put(hm, ids.cpu().numpy(), rows.cpu().numpy())
+    torch.cuda.synchronize()
+    del ids, rows
+    fetch = B.hps_hostmap_fetch_fn()
+    steps = max(1, min(a.steps, 5))
+    times, n = [], 0
+    for _ in range(steps):
+        t0 = _time.perf_counter()
+        n = B.hps_cache_refresh(h, 1 << 18, fetch, user=hm)
+        torch.cuda.synchronize()
+        times.append(_time.perf_counter() - t0)
+    ms = float(np.median(times)) * 1e3
+    gb = n * 4 * d / 1e9
+    res = {"metric": "cache refresh from a host-memory lower tier, GB/s of cached rows", "value": round(gb / (ms * 1e-3), 2), "unit": "GB/s",
+           "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": round(ms, 2), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"hps_cache_refresh: {n} cached rows of dim {d} ({gb:.2f} GB), batches of 262144 slots, lower tier = host map of {n_keys} keys",
+                      "Mkeys_per_s": round(n / (ms * 1e-3) / 1e6, 1)}}
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    B.hps_hostmap_destroy(hm)
+    print(json.dumps(res))
+
+
 def multi_table(a, np, torch, B, inputs):
     """26 independent caches (vocabulary log-uniform in [1e3, 1e8], each cache 20 % of its vocabulary,
     at most 2^22 slots), one Zipf(1.05) key per table and sample, 131072 samples, one launch."""
@@ -488,6 +531,8 @@ def main():
         return write_batches(a, np, torch, B, inputs)
     if a.workload == "lookup":
         return lookup_alg1(a, np, torch, B, inputs)
+    if a.workload == "refresh-host":
+        return refresh_from_host(a, np, torch, B, inputs)
 
     S, W, d = 1 << a.log2_sets, a.ways, a.dim
     slots = S * W

@@ -59,6 +59,20 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
 hps_status_t hps_lookup(hps_lookup_t *lookup, const int64_t *keys, size_t n, float *out,
                         float *hit_rate, int *was_synchronous, void *stream);
 
+/*
+ * The cache refresh cycle of the paper (Sec. 6, Fig. 3 steps 1-5): dump the cached keys in batches
+ * of `batch_slots` slots, look each batch up in the lower tiers through `fetch`, copy the rows to
+ * the device and Update the cache with them.  The dump and the copy of the keys to the host run on
+ * a stream of their own, so the host-side lookup of one batch overlaps the upload and Update of
+ * the previous one.  Returns when the whole cache has been refreshed; *n_refreshed (may be NULL)
+ * receives the number of keys that were dumped and updated.  Queries may run meanwhile (on other
+ * streams, with the cache in its concurrent-writer mode).  Keys that an overlapping insert evicts
+ * between dump and Update are skipped by the Update (Alg. 4).  batch_slots in 1 .. 2^31 - 1.
+ * The lower tier must hold every cached key: `fetch` has no way to say "not found".
+ */
+hps_status_t hps_cache_refresh(hps_cache_t *cache, size_t batch_slots, hps_fetch_fn fetch, void *user,
+                               size_t *n_refreshed, void *stream);
+
 /* Block until every queued asynchronous insertion has been applied to the cache. */
 hps_status_t hps_lookup_drain(hps_lookup_t *lookup);
 

@@ -30,6 +30,7 @@ EXPORTS = (
     "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
     "hps_cache_flags", "hps_cache_debug_set_seq", "hps_cache_query_dn",
     "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
+    "hps_cache_refresh",
     "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
     "hps_hostmap_create", "hps_hostmap_destroy", "hps_hostmap_put", "hps_hostmap_get", "hps_hostmap_fetch",
     "hps_hostmap_stats",
@@ -75,6 +76,7 @@ def load_library():
         "hps_lookup": [vp, vp, sz, vp, C.POINTER(C.c_float), C.POINTER(C.c_int), vp],
         "hps_lookup_drain": [vp],
         "hps_lookup_destroy": [vp],
+        "hps_cache_refresh": [vp, sz, FETCH_FN, vp, C.POINTER(sz), vp],
         "hps_dedup_create": [sz, C.POINTER(vp)],
         "hps_dedup_destroy": [vp],
         "hps_dedup": [vp, vp, sz, vp, vp, vp, vp],
@@ -281,6 +283,14 @@ def hps_lookup(lookup, keys, n, out, stream=None):
     _check_lookup(load_library().hps_lookup(lookup, _ptr(keys, torch.int64), n, _ptr(out, torch.float32),
                                             C.byref(rate), C.byref(sync), _stream(stream)))
     return rate.value, bool(sync.value)
+
+
+def hps_cache_refresh(cache, batch_slots: int, fetch, user=None, stream=None) -> int:
+    """The refresh cycle of Sec. 6 (dump, lower-tier lookup, upload, Update); returns the number
+    of keys refreshed."""
+    n = C.c_size_t()
+    _check_lookup(load_library().hps_cache_refresh(cache, batch_slots, fetch, user, C.byref(n), _stream(stream)))
+    return n.value
 
 
 def hps_lookup_drain(lookup) -> None:

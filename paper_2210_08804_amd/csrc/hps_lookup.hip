@@ -322,6 +322,86 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     return HPS_OK;
 }
 
+hps_status_t hps_cache_refresh(hps_cache_t *cache, size_t batch_slots, hps_fetch_fn fetch, void *user,
+                               size_t *n_refreshed, void *stream) {
+    if (n_refreshed) *n_refreshed = 0;
+    uint64_t sets = 0;
+    uint32_t ways = 0, dim = 0;
+    if (hps_cache_info(cache, &sets, &ways, &dim) != HPS_OK) return lfail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    if (!fetch) return lfail(HPS_ERR_INVALID_ARG, "fetch is required");
+    if (batch_slots == 0 || batch_slots >= (1ull << 31)) return lfail(HPS_ERR_INVALID_ARG, "batch_slots must be in [1, 2^31)");
+    const uint64_t slots = sets * ways;
+    const size_t B = batch_slots < slots ? batch_slots : (size_t)slots;
+    const size_t rowb = (size_t)dim * sizeof(float);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // two sets of buffers: the host looks batch i + 1 up while batch i is uploaded and applied
+    int64_t *d_keys[2] = {nullptr, nullptr}, *h_keys[2] = {nullptr, nullptr};
+    float *d_rows[2] = {nullptr, nullptr}, *h_rows[2] = {nullptr, nullptr};
+    uint32_t *d_cnt = nullptr, *h_cnt = nullptr;
+    hipStream_t s2 = nullptr;
+    hipEvent_t applied[2] = {nullptr, nullptr};
+    hipError_t e = hipSuccess;
+    for (int b = 0; b < 2; ++b) {
+        if (e == hipSuccess) e = hipMalloc((void **)&d_keys[b], B * 8);
+        if (e == hipSuccess) e = hipMalloc((void **)&d_rows[b], B * rowb);
+        if (e == hipSuccess) e = hipHostMalloc((void **)&h_keys[b], B * 8, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostMalloc((void **)&h_rows[b], B * rowb, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&applied[b], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipMalloc((void **)&d_cnt, 8);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&h_cnt, 8, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking);
+
+    size_t total = 0;
+    std::string err;
+    bool used[2] = {false, false};
+    for (uint64_t first = 0, i = 0; e == hipSuccess && err.empty() && first < slots; first += B, ++i) {
+        const int b = (int)(i & 1);
+        const size_t cnt_slots = (size_t)(slots - first < B ? slots - first : B);
+        if (used[b]) e = hipEventSynchronize(applied[b]);          // this pair of buffers is free again
+        if (e != hipSuccess) break;
+        if (hps_cache_dump(cache, (size_t)first, cnt_slots, d_keys[b], d_cnt + b, s2) != HPS_OK) {
+            err = std::string("dump: ") + hps_last_error();
+            break;
+        }
+        e = hipMemcpyAsync(h_cnt + b, d_cnt + b, 4, hipMemcpyDeviceToHost, s2);
+        if (e == hipSuccess) e = hipStreamSynchronize(s2);
+        if (e != hipSuccess) break;
+        const uint32_t m = h_cnt[b];
+        if (m == 0) continue;
+        e = hipMemcpyAsync(h_keys[b], d_keys[b], (size_t)m * 8, hipMemcpyDeviceToHost, s2);
+        if (e == hipSuccess) e = hipStreamSynchronize(s2);
+        if (e != hipSuccess) break;
+        fetch(user, h_keys[b], m, h_rows[b]);                       // steps 2-3: lower tiers, key-vector buffer
+        e = hipMemcpyAsync(d_rows[b], h_rows[b], (size_t)m * rowb, hipMemcpyHostToDevice, st);   // step 4
+        if (e != hipSuccess) break;
+        if (hps_cache_update(cache, d_keys[b], d_rows[b], m, st) != HPS_OK) {                    // step 5
+            err = std::string("update: ") + hps_last_error();
+            break;
+        }
+        e = hipEventRecord(applied[b], st);
+        used[b] = true;
+        total += m;
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (s2) (void)hipStreamSynchronize(s2);
+    for (int b = 0; b < 2; ++b) {
+        (void)hipFree(d_keys[b]); (void)hipFree(d_rows[b]);
+        (void)hipHostFree(h_keys[b]); (void)hipHostFree(h_rows[b]);
+        if (applied[b]) (void)hipEventDestroy(applied[b]);
+    }
+    (void)hipFree(d_cnt); (void)hipHostFree(h_cnt);
+    if (s2) (void)hipStreamDestroy(s2);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return lfail(e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE, std::string("hps_cache_refresh: ") + hipGetErrorString(e));
+    }
+    if (!err.empty()) return lfail(HPS_ERR_DEVICE, err);
+    if (n_refreshed) *n_refreshed = total;
+    return HPS_OK;
+}
+
 hps_status_t hps_lookup_drain(hps_lookup_t *L) {
     if (!L) return lfail(HPS_ERR_INVALID_ARG, "lookup is NULL");
     std::unique_lock<std::mutex> lk(L->mu);

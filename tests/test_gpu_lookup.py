@@ -13,7 +13,8 @@ import torch
 from oracle import OracleCache
 from paper_2210_08804_amd import binding as B
 from paper_2210_08804_amd import inputs
-from harness import DeviceCache, assert_same_state, check_state_invariants, insert_is_order_independent
+from harness import (DeviceCache, SENTINEL, assert_same_state, check_state_invariants,
+                     insert_is_order_independent)
 
 pytestmark = pytest.mark.gpu
 
@@ -226,3 +227,71 @@ def test_a_lower_tier_that_falls_far_behind_loses_the_oldest_batches_only():
             assert rate == 1.0 and not sync
         finally:
             B.hps_lookup_destroy(lk)
+
+
+@pytest.mark.parametrize("batch_slots", [1000, 4096, 1 << 20])
+def test_refresh_cycle_from_the_host_map(batch_slots):
+    """Sec. 6, Fig. 3 steps 1-5 through hps_cache_refresh: every cached key gets the row the lower
+    tier holds now; nothing else changes (same keys, same counters)."""
+    S, W, d = 1 << 10, 8, 32
+    keys = np.unique(inputs.uniform_keys(6000, 1 << 30, 91))
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        oc = OracleCache(S * W, W, d)
+        for ck in np.array_split(keys, 4):
+            gc.insert(ck, inputs.backing_rows(ck, d, 0))
+        oc.load_state(*gc.export())
+        cached = oc.dump()
+        hm = B.hps_hostmap_create(d, 8, len(keys))
+        try:
+            B.hps_hostmap_put(hm, keys, inputs.backing_rows(keys, d, 1))          # the lower tier has moved on
+            n = B.hps_cache_refresh(gc.h, batch_slots, B.hps_hostmap_fetch_fn(), user=hm)
+            torch.cuda.synchronize()
+            assert n == len(cached)
+            oc.update(cached, inputs.backing_rows(cached, d, 1))
+            assert_same_state(gc.export(), oc)
+            assert B.hps_hostmap_stats(hm)[1] == 0                               # only stored keys were asked for
+        finally:
+            B.hps_hostmap_destroy(hm)
+
+
+def test_refresh_cycle_overlapping_queries_returns_whole_rows():
+    S, W, d, n_q = 1 << 12, 8, 64, 20000
+    keys = np.unique(inputs.uniform_keys(30000, 1 << 30, 92))
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        for ck in np.array_split(keys, 8):
+            gc.insert(ck, inputs.backing_rows(ck, d, 0))
+        hm = B.hps_hostmap_create(d, 8, len(keys))
+        try:
+            B.hps_hostmap_put(hm, keys, inputs.backing_rows(keys, d, 1))
+            qs = torch.cuda.Stream()
+            rs = torch.cuda.Stream()
+            q = keys[np.random.Generator(np.random.PCG64(5)).integers(0, len(keys), n_q)]
+            dq = torch.from_numpy(q).cuda()
+            outs = [torch.full((n_q, d), SENTINEL, dtype=torch.int32, device="cuda").view(torch.float32) for _ in range(40)]
+            mi = torch.empty(n_q, dtype=torch.int32, device="cuda")
+            mk = torch.empty(n_q, dtype=torch.int64, device="cuda")
+            nm = torch.zeros(40, dtype=torch.int32, device="cuda")
+            torch.cuda.synchronize()
+            import threading
+            t = threading.Thread(target=lambda: B.hps_cache_refresh(gc.h, 2048, B.hps_hostmap_fetch_fn(), user=hm, stream=rs))
+            t.start()
+            for i in range(40):
+                B.hps_cache_query(gc.h, dq, n_q, outs[i], mi, mk, nm[i:i + 1], qs)
+            t.join()
+            torch.cuda.synchronize()
+            v0 = inputs.backing_rows(q, d, 0).view(np.uint32)
+            v1 = inputs.backing_rows(q, d, 1).view(np.uint32)
+            seen_new = 0
+            for i in range(40):
+                o = outs[i].view(torch.int32).cpu().numpy().view(np.uint32)
+                hit = ~(o == SENTINEL).all(axis=1)
+                is0 = (o == v0).all(axis=1)
+                is1 = (o == v1).all(axis=1)
+                assert (is0 | is1)[hit].all(), "a row is neither the old nor the new version"
+                seen_new += int(is1[hit].sum())
+            got, mi2, _ = gc.query(q)
+            hit = np.ones(n_q, dtype=bool)
+            hit[mi2] = False
+            assert (got[hit] == v1[hit]).all()                                   # after the refresh everything is new
+        finally:
+            B.hps_hostmap_destroy(hm)
