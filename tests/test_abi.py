@@ -59,7 +59,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.hps_backing_fetch(None, 5, None, 8, 0, None, None, None, None) == -1   # keys NULL
     assert lib.hps_cache_query_dn(None, None, 0, None, None, None, None, None, None) == -1
     assert lib.hps_lookup(None, None, 0, None, None, None, None) == -1
-    assert lib.hps_cache_refresh(None, 10, None, None, None, None) == -1
+    from paper_2210_08804_amd import binding
+    assert lib.hps_cache_refresh(None, 10, binding.FETCH_FN(), None, None, None) == -1
     assert lib.hps_lookup_drain(None) == -1 and lib.hps_lookup_destroy(None) == -1
     assert len(lib.hps_lookup_last_error()) > 0
     assert lib.hps_dedup_create(0, C.byref(h)) == -1 and lib.hps_dedup_create(1 << 31, C.byref(h)) == -1
