@@ -7,7 +7,6 @@
 #include <mutex>
 #include <new>
 #include <thread>
-#include <unordered_map>
 #include <vector>
 
 #include "hps_hostmap.h"
@@ -27,11 +26,41 @@ uint64_t mix64(uint64_t x) {
     return x;
 }
 
+constexpr uint64_t kFree = ~0ull;                 // row number of an unused slot
+
+// Open-addressing index of one partition: key -> row number, linear probing, at most half full.
+// (One cache line per lookup in the common case; a node-based map costs two.)
+struct Slot {
+    int64_t  key;
+    uint64_t row;
+};
+
 struct Partition {
     std::mutex mu;
-    std::unordered_map<int64_t, uint64_t> index;      // key -> row number in this partition
+    std::vector<Slot> table;                          // size is a power of two
     std::vector<float *> slabs;                       // kSlabRows rows each
     uint64_t n_rows = 0;
+
+    static uint64_t home(int64_t key, uint64_t mask) { return (mix64((uint64_t)key) >> 8) & mask; }
+
+    // slot of `key`, or the free slot where it would go
+    uint64_t find(int64_t key) const {
+        const uint64_t mask = table.size() - 1;
+        uint64_t i = home(key, mask);
+        while (table[i].row != kFree && table[i].key != key) i = (i + 1) & mask;
+        return i;
+    }
+
+    void reserve_slots(uint64_t n_keys) {             // table of at least 2 * n_keys slots
+        uint64_t want = 1024;
+        while (want < 2 * n_keys) want <<= 1;
+        if (want <= table.size()) return;
+        std::vector<Slot> old;
+        old.swap(table);
+        table.assign(want, Slot{0, kFree});
+        for (const Slot &sl : old)
+            if (sl.row != kFree) table[find(sl.key)] = sl;
+    }
 };
 
 }  // namespace
@@ -87,13 +116,16 @@ size_t get_range(hps_hostmap *m, const int64_t *keys, size_t n, float *rows,
         if (mine.empty()) continue;
         Partition &P = m->parts[p];
         std::lock_guard<std::mutex> lk(P.mu);
-        for (size_t i : mine) {
-            auto it = P.index.find(keys[i]);
-            if (it == P.index.end()) {
+        const uint64_t mask = P.table.size() - 1;
+        for (size_t j = 0; j < mine.size(); ++j) {
+            if (j + 4 < mine.size()) __builtin_prefetch(&P.table[Partition::home(keys[mine[j + 4]], mask)]);
+            const size_t i = mine[j];
+            const Slot &sl = P.table[P.find(keys[i])];
+            if (sl.row == kFree) {
                 std::memset(rows + i * m->dim, 0, sizeof(float) * m->dim);
                 ++absent;
             } else {
-                std::memcpy(rows + i * m->dim, row_ptr(m, P, it->second), sizeof(float) * m->dim);
+                std::memcpy(rows + i * m->dim, row_ptr(m, P, sl.row), sizeof(float) * m->dim);
             }
         }
     }
@@ -134,7 +166,7 @@ hps_status_t hps_hostmap_create(uint32_t dim, uint32_t partitions, size_t reserv
         m->dim = dim;
         m->n_part = partitions;
         m->parts = std::vector<Partition>(partitions);
-        for (auto &p : m->parts) p.index.reserve(reserve / partitions + 16);
+        for (auto &p : m->parts) p.reserve_slots(reserve / partitions + 16);
     } catch (const std::bad_alloc &) {
         delete m;
         return HPS_ERR_OOM;
@@ -179,15 +211,19 @@ hps_status_t hps_hostmap_put(hps_hostmap_t *m, const int64_t *keys, const float 
         for (size_t i = 0; i < n; ++i) {
             Partition &P = m->parts[part_of(m, keys[i])];
             std::lock_guard<std::mutex> lk(P.mu);
-            auto it = P.index.find(keys[i]);
+            uint64_t at = P.find(keys[i]);
             uint64_t r;
-            if (it == P.index.end()) {
+            if (P.table[at].row == kFree) {
+                if (2 * (P.n_rows + 1) > P.table.size()) {       // keep the table at most half full
+                    P.reserve_slots(P.n_rows + 1);
+                    at = P.find(keys[i]);
+                }
                 r = P.n_rows;
                 if (r / kSlabRows >= P.slabs.size()) P.slabs.push_back(new float[kSlabRows * (size_t)m->dim]);
-                P.index.emplace(keys[i], r);
+                P.table[at] = Slot{keys[i], r};
                 ++P.n_rows;
             } else {
-                r = it->second;
+                r = P.table[at].row;
             }
             std::memcpy(row_ptr(m, P, r), rows + i * m->dim, sizeof(float) * m->dim);
         }
@@ -246,7 +282,7 @@ hps_status_t hps_hostmap_stats(hps_hostmap_t *m, size_t *n_keys, size_t *n_absen
         size_t k = 0;
         for (auto &p : m->parts) {
             std::lock_guard<std::mutex> lk(p.mu);
-            k += p.index.size();
+            k += p.n_rows;
         }
         *n_keys = k;
     }
