@@ -1,6 +1,7 @@
 // Algorithm 1 of the paper (embedding cache insertion: hit-rate test, synchronous or asynchronous
-// fill) on top of the C ABI of the cache.  Host orchestration plus two small kernels; the lower
-// tiers are a caller-supplied fetch callback working on pinned host buffers.
+// fill) and the cache refresh cycle of its Sec. 6, on top of the C ABI of the cache and of the
+// dedup operator.  Host orchestration plus one small kernel; the lower tiers are a caller-supplied
+// fetch callback working on pinned host buffers.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
