@@ -295,3 +295,64 @@ def test_refresh_cycle_overlapping_queries_returns_whole_rows():
             assert (got[hit] == v1[hit]).all()                                   # after the refresh everything is new
         finally:
             B.hps_hostmap_destroy(hm)
+
+
+@pytest.mark.parametrize("threshold", [2.0, 0.7])
+def test_three_lookup_objects_on_three_threads_share_one_cache(threshold):
+    """Several inference workers share the GPU's embedding cache (Sec. 3.1, Sec. 7.2.2): three
+    threads, each with its own lookup object and stream, look batches up at the same time.  In
+    synchronous mode every row must be its key's row; in the mixed mode a row is its key's row or
+    the default row; afterwards the cache state is a legal one."""
+    import threading
+    S, W, d, n, space, steps = 1 << 12, 8, 32, 4000, 60000, 12
+    default_row = np.full(d, -3.0, dtype=np.float32)
+    all_keys = np.arange(space, dtype=np.int64)
+    hm = B.hps_hostmap_create(d, 16, space)
+    B.hps_hostmap_put(hm, all_keys, inputs.backing_rows(all_keys, d, 0))
+    fetch = B.hps_hostmap_fetch_fn()
+    errors = []
+    with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
+        lks = [B.hps_lookup_create(gc.h, n, threshold, default_row, fetch, user=hm) for _ in range(3)]
+
+        def worker(t):
+            try:
+                torch.cuda.set_device(0)
+                st = torch.cuda.Stream()
+                for step in range(steps):
+                    keys = inputs.zipf_keys(n, space, 1.1, 1000 * t + step)
+                    dk = torch.from_numpy(keys).cuda()
+                    out = torch.zeros(n, d, dtype=torch.float32, device="cuda")
+                    torch.cuda.synchronize()
+                    rate, sync = B.hps_lookup(lks[t], dk, n, out, st)
+                    st.synchronize()
+                    got = out.cpu().numpy().view(np.uint32)
+                    exp = inputs.backing_rows(keys, d, 0).view(np.uint32)
+                    right = (got == exp).all(axis=1)
+                    dflt = (got == default_row.view(np.uint32)).all(axis=1)
+                    if threshold > 1.0 and not right.all():
+                        errors.append(f"thread {t} step {step}: {int((~right).sum())} wrong rows in synchronous mode")
+                    if not (right | dflt).all():
+                        errors.append(f"thread {t} step {step}: a row is neither its key's row nor the default row")
+                    if not 0.0 <= rate <= 1.0:
+                        errors.append(f"thread {t}: hit rate {rate}")
+            except Exception as exc:                         # noqa: BLE001 - reported by the main thread
+                errors.append(f"thread {t}: {exc!r}")
+
+        threads = [threading.Thread(target=worker, args=(t,)) for t in range(3)]
+        try:
+            for th in threads:
+                th.start()
+            for th in threads:
+                th.join()
+            for lk in lks:
+                B.hps_lookup_drain(lk)
+            torch.cuda.synchronize()
+            assert not errors, errors[:5]
+            oc = OracleCache(S * W, W, d)
+            check_state_invariants(*gc.export(), oc.set_of,
+                                   expect_row=lambda k: [inputs.backing_rows(np.array([k]), d, 0).view(np.uint32)[0]])
+            assert B.hps_hostmap_stats(hm)[1] == 0
+        finally:
+            for lk in lks:
+                B.hps_lookup_destroy(lk)
+            B.hps_hostmap_destroy(hm)
