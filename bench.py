@@ -55,6 +55,8 @@ def parse():
     p.add_argument("--streams", type=int, default=3,
                    help="also time the same batches issued round-robin over this many streams (0: skip)")
     p.add_argument("--threshold", type=float, default=0.8, help="lookup: hit-rate threshold t of Alg. 1")
+    p.add_argument("--instances", type=int, default=1,
+                   help="lookup: concurrent workers (threads), each with its own lookup object and stream, on one cache")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-batches", type=int, default=100)
     p.add_argument("--calibrate-copy", action="store_true",
@@ -295,6 +297,59 @@ def write_batches(a, np, torch, B, inputs):
     print(json.dumps(res))
 
 
+def _lookup_instances(a, np, torch, B, inputs, h, hm, fetch, n, space, S, W, d, steps):
+    """Several inference workers on one cache (Sec. 7.2.2): each thread has its own lookup object,
+    stream and key stream; `value` is the aggregate rate over the second half of the calls."""
+    import threading
+    import time as _time
+    k = a.instances
+    lks = [B.hps_lookup_create(h, n, a.threshold, np.zeros(d, np.float32), fetch, user=hm) for _ in range(k)]
+    keys = [[torch.from_numpy(inputs.zipf_keys(n, space, 1.2, 1000 * t + s + 1)).cuda() for s in range(steps)] for t in range(k)]
+    outs = [torch.empty(n, d, dtype=torch.float32, device="cuda") for _ in range(k)]
+    torch.cuda.synchronize()
+    stamps = [[0.0] * (steps + 1) for _ in range(k)]
+    rates = [[0.0] * steps for _ in range(k)]
+    barrier = threading.Barrier(k)
+
+    def worker(t):
+        torch.cuda.set_device(0)
+        st = torch.cuda.Stream()
+        barrier.wait()
+        stamps[t][0] = _time.perf_counter()
+        for s in range(steps):
+            r, _ = B.hps_lookup(lks[t], keys[t][s], n, outs[t], st)
+            st.synchronize()
+            stamps[t][s + 1] = _time.perf_counter()
+            rates[t][s] = r
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(k)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    for lk in lks:
+        B.hps_lookup_drain(lk)
+    half = steps // 2
+    t_begin = min(stamps[t][half] for t in range(k))
+    t_end = max(stamps[t][steps] for t in range(k))
+    lat = np.array([stamps[t][s + 1] - stamps[t][s] for t in range(k) for s in range(half, steps)]) * 1e3
+    value = k * n * (steps - half) / (t_end - t_begin) / 1e6
+    res = {"metric": "Alg. 1 lookup Mkeys/s, several workers on one cache (stable stage, aggregate)", "value": round(value, 1),
+           "unit": "Mkeys/s", "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": round(float(lat.mean()), 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+           "config": {"workload": f"{k} threads x hps_lookup: {n} Zipf(1.2) keys per call over {space} keys, one cache of {S} sets x {W} ways x dim {d}, "
+                                  f"threshold {a.threshold}, lower tier = host map", "replacement_policy": a.policy, "instances": k,
+                      "latency_ms_stable": {"mean": round(float(lat.mean()), 4), "p50": round(float(np.median(lat)), 4),
+                                            "p99": round(float(np.percentile(lat, 99)), 4)},
+                      "hit_rate_stable": round(float(np.mean([rates[t][s] for t in range(k) for s in range(half, steps)])), 4)}}
+    for lk in lks:
+        B.hps_lookup_destroy(lk)
+    torch.cuda.synchronize()
+    B.hps_cache_destroy(h)
+    B.hps_hostmap_destroy(hm)
+    print(json.dumps(res))
+
+
 def lookup_alg1(a, np, torch, B, inputs):
     """Algorithm 1 end to end: hps_lookup on a cold cache with the library's host map as the lower
     tier (2^22 keys x dim fp32 in host memory), cache = 5 % of the key space, batches of
@@ -319,6 +374,8 @@ def lookup_alg1(a, np, torch, B, inputs):
     h = (B.hps_cache_create(S * W, W, d) if a.policy == "counter"
          else B.hps_cache_create_policy(S * W, W, d, B.HPS_POLICY_LRU))
     fetch = B.hps_hostmap_fetch_fn()
+    if a.instances > 1:
+        return _lookup_instances(a, np, torch, B, inputs, h, hm, fetch, n, space, S, W, d, steps)
     lk = B.hps_lookup_create(h, n, a.threshold, np.zeros(d, np.float32), fetch, user=hm)
     keys = [torch.from_numpy(inputs.zipf_keys(n, space, 1.2, s + 1)).cuda() for s in range(steps)]
     out = torch.empty(n, d, dtype=torch.float32, device="cuda")
