@@ -172,7 +172,10 @@ hps_status_t hps_cache_import(hps_cache_t *cache, const int64_t *keys, const uin
 
 /*
  * LRU caches only: the access stamps (stamps [device, sets*ways uint32], [set][way] order) and
- * the global iteration count (*g [host] on export).  Complements hps_cache_export/import.
+ * the global iteration count g of Alg. 2, which lives in a device word of the cache: the query
+ * kernel advances it (so a query captured into a HIP graph advances it on every replay) and the
+ * insert kernel reads it.  Export copies it to *g [host] and, for that, waits for `stream`;
+ * import sets it in stream order.  Complements hps_cache_export/import.
  */
 hps_status_t hps_cache_export_lru(hps_cache_t *cache, uint32_t *stamps, uint32_t *g, void *stream);
 hps_status_t hps_cache_import_lru(hps_cache_t *cache, const uint32_t *stamps, uint32_t g, void *stream);

@@ -34,7 +34,7 @@ extern "C" {
 
 typedef struct hps_dedup_session hps_dedup_t;
 
-/* Create a session for batches of up to max_n keys (0 < max_n < 2^31) on the current device.
+/* Create a session for batches of up to max_n keys (0 < max_n <= 2^30) on the current device.
  * Allocates three hash tables of the next power of two >= 2 * max_n slots each (12 bytes per
  * slot): two that alternate between calls, one for calls captured into a HIP graph.
  * Errors: HPS_ERR_INVALID_ARG, HPS_ERR_OOM, HPS_ERR_DEVICE; *out is NULL on failure. */

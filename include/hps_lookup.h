@@ -38,7 +38,7 @@ typedef void (*hps_fetch_fn)(void *user, const int64_t *keys, size_t n, float *r
  * cache           the cache to serve from; it must allow concurrent writers
  *                 (hps_cache_set_concurrent_writers(cache, 1), the default) because background
  *                 inserts overlap later queries.
- * max_batch       largest n a lookup call may pass (1 .. 2^31 - 1).
+ * max_batch       largest n a lookup call may pass (1 .. 2^30).
  * hit_threshold   t of Alg. 1: hit rate < t selects synchronous insertion.  0 = always
  *                 asynchronous, anything above 1 = always synchronous.
  * default_row     [host, dim fp32] vector handed out for missing keys in asynchronous mode.
@@ -50,8 +50,9 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
 
 /*
  * One pass of Alg. 1.  keys [device, n int64], out [device, n*dim fp32], stream as in hps_cache.h.
- * Hit rate = 1 - misses / n per position (Alg. 1 prints "/ N = total size of embedding cache",
- * which cannot be meant).  On return every row of out is either its key's cached row, its fetched
+ * Hit rate = 1 - misses / n per position, computed and compared with the threshold in single
+ * precision (a deliberate reading of the hit-rate step of Alg. 1, whose divisor is declared as the
+ * capacity of the cache).  On return every row of out is either its key's cached row, its fetched
  * row (synchronous mode) or the default row (asynchronous mode), in stream order: the call
  * synchronises the host with `stream` once, to read the miss count, as Alg. 1 needs it.
  * *hit_rate [host] and *was_synchronous [host] may be NULL.

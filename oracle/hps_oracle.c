@@ -20,6 +20,10 @@
  *   - Deduplication, Sec. 2.2: Q* = dedup(Q), the distinct keys of a query batch, with the map
  *     from every position of Q to its key's place in Q* (what a caller needs to hand every
  *     position its row after looking up Q* only).
+ *   - Embedding cache insertion, Sec. 4.3 and Alg. 1: look the batch up, compute the hit rate,
+ *     and below the threshold fetch the missing vectors from the lower tiers, insert them and
+ *     return them (synchronous insertion); otherwise return the default vector for the missing
+ *     keys and insert the fetched vectors afterwards (asynchronous insertion).
  *
  * Readings where the paper is silent or differs from this build's contract:
  *   - Geometry: a set has W slots (W a power of two, 1..64); the paper's 32-slot slabs and
@@ -40,7 +44,17 @@
  *     query reports them as misses, insert and update skip them.
  *   - Duplicates in a batch are handled by plain index order: every missing position gets
  *     its own miss-list entry; the first occurrence of a new key inserts, later ones find it.
- *   - Rows are opaque 32-bit patterns (no floating-point arithmetic anywhere).
+ *   - Rows are opaque 32-bit patterns (no floating-point arithmetic anywhere on the cache path).
+ *   - Alg. 1: the hit rate is 1 - |missing| / |Q| per position (the listing divides by "N = total
+ *     size of embedding cache", which cannot be meant); it is computed and compared with the
+ *     threshold t in single precision, the precision the product's call takes the decision in;
+ *     "hit rate < t" selects synchronous insertion, so a hit rate equal to t is asynchronous.
+ *     The lookup is per position (the C ABI takes Q, not Q*); what is fetched and inserted is the
+ *     distinct missing keys in order of first occurrence.  The lower tiers are an input: the
+ *     caller passes the vector they hold for every position's key.  The asynchronous task is
+ *     modelled as having run to completion when the call returns (the tests drain the product's
+ *     queue before they compare), so both modes leave the same cache state and differ only in
+ *     the rows handed out for the missing positions.
  *   - dedup: the paper fixes no order of Q*; here it is the order of first occurrence (any
  *     permutation of Q* with the matching map is an equally valid result).  All 2^64 key values
  *     are ordinary to dedup, the two reserved ones included.
@@ -82,6 +96,12 @@ uint64_t hpso_set_of(const hpso_t *c, int64_t key)
 {
     uint32_t h = (uint32_t)(hpso_mix64((uint64_t)key) >> 32);
     return (uint64_t)h % c->S;
+}
+
+/* The same for a batch of keys (test plumbing: no per-key call from Python). */
+void hpso_sets_of(const hpso_t *c, const int64_t *keys, uint64_t n, uint64_t *sets_out)
+{
+    for (uint64_t i = 0; i < n; ++i) sets_out[i] = hpso_set_of(c, keys[i]);
 }
 
 static int is_reserved(int64_t key)
@@ -252,4 +272,63 @@ void hpso_expand(const uint32_t *rows, const uint32_t *inverse, uint64_t n, uint
 {
     for (uint64_t i = 0; i < n; ++i)
         memcpy(out + i * d, rows + (uint64_t)inverse[i] * d, sizeof(uint32_t) * d);
+}
+
+/*
+ * One pass of Alg. 1 (embedding cache insertion) for the batch Q = keys[0..n).
+ *   lower[i*d .. i*d+d)  the vector the lower tiers hold for keys[i] (ParServerLookup's answer)
+ *   t                    hit rate threshold
+ *   default_row[d]       vector handed out for missing keys in asynchronous mode
+ *   out[n][d]            E_Q: cached vector on a hit; on a miss the fetched vector (synchronous)
+ *                        or the default vector (asynchronous)
+ *   ins_keys[<= n]       receives the distinct missing keys in order of first occurrence: what
+ *                        ParServerLookup is asked for and what is inserted
+ * Returns the number of distinct missing keys; *hit_rate and *synchronous describe the decision.
+ * When do_insert is zero the cache is left as the lookup found it (the caller inserts ins_keys
+ * itself, e.g. after classifying the batch); otherwise the insertion is done here.
+ */
+uint64_t hpso_lookup(hpso_t *c, const int64_t *keys, uint64_t n, const uint32_t *lower, float t,
+                     const uint32_t *default_row, uint32_t *out, float *hit_rate, int *synchronous,
+                     int64_t *ins_keys, int do_insert)
+{
+    *hit_rate = 1.0f;
+    *synchronous = 0;
+    if (n == 0) return 0;
+    /* EmbCacheLookup(Q): hits land in E_Q, misses in the workspace */
+    uint32_t *miss_idx  = (uint32_t *)malloc(sizeof(uint32_t) * n);
+    int64_t  *miss_keys = (int64_t *)malloc(sizeof(int64_t) * n);
+    uint32_t *ins_rows  = (uint32_t *)malloc(sizeof(uint32_t) * n * c->d);
+    if (!miss_idx || !miss_keys || !ins_rows) abort();
+    uint64_t m = hpso_query(c, keys, n, out, miss_idx, miss_keys);
+    /* hitRate <- 1 - |missingKeys| / |Q| */
+    float rate = 1.0f - (float)m / (float)n;
+    *hit_rate = rate;
+    uint64_t u = 0;
+    if (m > 0) {
+        /* ParServerLookup(missingKeys): each missing key once, with the vector of the lower tiers */
+        for (uint64_t j = 0; j < m; ++j) {
+            uint64_t e = 0;
+            while (e < u && ins_keys[e] != miss_keys[j]) ++e;
+            if (e == u) {
+                ins_keys[u] = miss_keys[j];
+                memcpy(ins_rows + u * c->d, lower + (uint64_t)miss_idx[j] * c->d, sizeof(uint32_t) * c->d);
+                ++u;
+            }
+        }
+        if (rate < t) {
+            /* synchronous insertion: E_Q <- the fetched vectors */
+            *synchronous = 1;
+            for (uint64_t j = 0; j < m; ++j)
+                memcpy(out + (uint64_t)miss_idx[j] * c->d, lower + (uint64_t)miss_idx[j] * c->d,
+                       sizeof(uint32_t) * c->d);
+        } else {
+            /* asynchronous insertion: E_Q <- default values now, the insertion is queued */
+            for (uint64_t j = 0; j < m; ++j)
+                memcpy(out + (uint64_t)miss_idx[j] * c->d, default_row, sizeof(uint32_t) * c->d);
+        }
+        /* EmbCacheInsert(missingKeys, vectors): at once, or by the queued task */
+        if (do_insert) hpso_insert(c, ins_keys, ins_rows, u);
+    }
+    free(miss_idx); free(miss_keys); free(ins_rows);
+    return u;
 }

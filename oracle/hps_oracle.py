@@ -39,6 +39,8 @@ def load_library(path=None):
     lib.hpso_destroy.argtypes = [vp]
     lib.hpso_set_of.restype = u64
     lib.hpso_set_of.argtypes = [vp, C.c_int64]
+    lib.hpso_sets_of.restype = None
+    lib.hpso_sets_of.argtypes = [vp, vp, u64, vp]
     lib.hpso_num_sets.restype = u64
     lib.hpso_num_sets.argtypes = [vp]
     for name in ("hpso_keys", "hpso_vals", "hpso_ctr", "hpso_stamps"):
@@ -56,6 +58,9 @@ def load_library(path=None):
     lib.hpso_dedup.argtypes = [vp, u64, vp, vp]
     lib.hpso_expand.restype = None
     lib.hpso_expand.argtypes = [vp, vp, u64, u32, vp]
+    lib.hpso_lookup.restype = u64
+    lib.hpso_lookup.argtypes = [vp, vp, u64, vp, C.c_float, vp, vp, C.POINTER(C.c_float),
+                                C.POINTER(C.c_int), vp, C.c_int]
     if path is None:
         _lib = lib
     return lib
@@ -133,6 +138,13 @@ class OracleCache:
     def set_of(self, key: int) -> int:
         return int(self._lib.hpso_set_of(self._h, C.c_int64(key)))
 
+    def sets_of(self, keys) -> np.ndarray:
+        """Set index of every key of a batch (int64 array)."""
+        keys = _keys(keys)
+        out = np.empty(keys.shape[0], dtype=np.uint64)
+        self._lib.hpso_sets_of(self._h, keys.ctypes.data, keys.shape[0], out.ctypes.data)
+        return out.astype(np.int64)
+
     def query(self, keys, out=None):
         """Returns (out, miss_idx, miss_keys).  `out` ([n, d] uint32) keeps its miss rows."""
         keys = _keys(keys)
@@ -156,6 +168,21 @@ class OracleCache:
         keys = _keys(keys)
         rows = _rows(rows, keys.shape[0], self.d)
         self._lib.hpso_update(self._h, keys.ctypes.data, rows.ctypes.data, keys.shape[0])
+
+    def lookup(self, keys, lower_rows, threshold, default_row, do_insert=True):
+        """One pass of Alg. 1.  lower_rows[i] is the vector the lower tiers hold for keys[i].
+        Returns (out, hit_rate as float32, synchronous, distinct missing keys in first-occurrence order)."""
+        keys = _keys(keys)
+        n = keys.shape[0]
+        lower = _rows(lower_rows, n, self.d)
+        dflt = _rows(np.asarray(default_row).reshape(1, -1), 1, self.d)
+        out = np.zeros((n, self.d), dtype=np.uint32)
+        ins = np.empty(max(n, 1), dtype=np.int64)
+        rate, sync = C.c_float(), C.c_int()
+        u = self._lib.hpso_lookup(self._h, keys.ctypes.data, n, lower.ctypes.data, C.c_float(threshold),
+                                  dflt.ctypes.data, out.ctypes.data, C.byref(rate), C.byref(sync),
+                                  ins.ctypes.data, 1 if do_insert else 0)
+        return out, np.float32(rate.value), bool(sync.value), ins[:u].copy()
 
     def dump(self):
         buf = np.empty(self.S * self.W, dtype=np.int64)

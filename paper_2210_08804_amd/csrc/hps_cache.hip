@@ -28,6 +28,7 @@
 #include <unordered_map>
 
 #include "hps_cache.h"
+#include "hps_mix.h"
 
 namespace {
 
@@ -61,15 +62,6 @@ hps_status_t fail(hps_status_t code, const std::string &msg) {
     } while (0)
 
 // ------------------------------------------------------------------ device helpers
-
-__device__ __forceinline__ uint64_t mix64(uint64_t x) {
-    x ^= x >> 30;
-    x *= 0xBF58476D1CE4E5B9ull;
-    x ^= x >> 27;
-    x *= 0x94D049BB133111EBull;
-    x ^= x >> 31;
-    return x;
-}
 
 // Alg. 2 "slabsetHasher(q) mod |S|": upper hash half modulo the set count (mask when S is 2^k).
 __device__ __forceinline__ uint32_t set_of(int64_t key, uint32_t S, uint32_t smask) {
@@ -106,46 +98,18 @@ template <typename T> __device__ __forceinline__ void st_agent(T *p, T v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Data that kernels overlapping on different streams share (keys, rows, counters of the cache)
-// is accessed in one of two ways, chosen at compile time:
-//   HPS_SCOPED_ACCESS = 1 (default): every such load/store is itself an agent-scope relaxed
-//     atomic of 4 or 8 bytes (the hardware then bypasses non-coherent cache copies), and the
-//     order "sequence word, then data, then sequence word" is kept by waiting until the wave's
-//     outstanding vector memory operations have completed (s_waitcnt vmcnt(0)) between the steps.
-//   HPS_SCOPED_ACCESS = 0: plain accesses between agent-scope acquire/release fences, which
-//     invalidate / write back whole caches and cost several times more.
-#ifndef HPS_SCOPED_ACCESS
-#define HPS_SCOPED_ACCESS 1
-#endif
-
-__device__ __forceinline__ void shared_acquire() {
-#if HPS_SCOPED_ACCESS
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#else
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
-}
-__device__ __forceinline__ void shared_release() {
-#if HPS_SCOPED_ACCESS
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#else
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-#endif
-}
-__device__ __forceinline__ uint64_t shared_ld64(const uint64_t *p) {
-#if HPS_SCOPED_ACCESS
-    return ld_agent(p);
-#else
-    return *p;
-#endif
-}
-__device__ __forceinline__ void shared_st64(uint64_t *p, uint64_t v) {
-#if HPS_SCOPED_ACCESS
-    st_agent(p, v);
-#else
-    *p = v;
-#endif
-}
+// Data that kernels overlapping on different streams share (keys, rows, counters of the cache):
+// every such load/store is itself an agent-scope relaxed atomic of 4 or 8 bytes (global_load /
+// global_store with sc1: the access is performed at the memory side of the non-coherent per-XCD
+// L2s, so it sees and is seen by every other agent-scope access of the device), and the order
+// "sequence word, then data, then sequence word" is kept by waiting until the wave's outstanding
+// vector memory operations have completed (s_waitcnt vmcnt(0)) between the steps: a wave's vector
+// memory instruction counter reaches zero only when every earlier load has returned its data and
+// every earlier store has been acknowledged by the level it was addressed to.
+__device__ __forceinline__ void shared_acquire() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void shared_release() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ uint64_t shared_ld64(const uint64_t *p) { return ld_agent(p); }
+__device__ __forceinline__ void shared_st64(uint64_t *p, uint64_t v) { st_agent(p, v); }
 
 struct Table {                 // one cache as the kernels see it
     int64_t  *K;
@@ -154,7 +118,7 @@ struct Table {                 // one cache as the kernels see it
     uint32_t  S;
     uint32_t  smask;           // S - 1 when S is a power of two, else 0
     uint32_t *T;               // [S][W] access stamps, LRU policy only (else nullptr)
-    uint32_t  g;               // the call's global iteration count (LRU policy)
+    uint32_t *gdev;            // the cache's global iteration count g of Alg. 2 (LRU policy): one device word
     uint32_t *flags;           // one word of HPS_FLAG_* bits raised by kernels
 };
 
@@ -366,8 +330,22 @@ struct QueryArgs {
     uint32_t       kpw;         // keys per worker wave (<= 64): lanes kpw..63 of a worker wave stay idle
     uint32_t       tiles_per_table;
     uint32_t       n_tiles;     // T * tiles_per_table (>= 1 even when B == 0)
+    uint32_t       n_tables;    // T (<= HPS_MAX_TABLES <= 64: one helper lane per table finishes the call)
     RowGeom        g;
 };
+
+// What the tile that finds every other tile of its call finished does (helper wave, all lanes):
+// publish the miss count, clear the call's counter word for the next call on the stream, and
+// advance the iteration count g of every LRU table of the call (Alg. 2 has thread 0 do the
+// atomic add; every tile has read g by then, because a tile reads it before it adds its count).
+__device__ __forceinline__ void finish_call(const QueryArgs &a, uint32_t n_miss, int lane) {
+    if (lane == 0) {
+        *a.n_miss = n_miss;
+        __hip_atomic_store(a.slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if ((uint32_t)lane < a.n_tables && a.tab[lane].T)
+        __hip_atomic_fetch_add(a.tab[lane].gdev, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Query (Alg. 2).  A work-group is WPB worker waves plus one helper wave and handles tiles of
 // WPB*KPW positions; the first KPW lanes of each worker wave own one key each.
@@ -406,6 +384,9 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
         const uint32_t lt = tile - t * a.tiles_per_table;
         if (wave < WPB) {
             const Table   &tb   = a.tab[t];
+            // Alg. 2 "g <- g + 1": every tile of the call stamps with the count the call will leave
+            // behind; the tile that finishes the call stores it (see the helper wave below).
+            const uint32_t g_call = tb.T ? *tb.gdev + 1u : 0u;
             const uint32_t b    = (lt * WPB + wave) * a.kpw + lane;
             const bool     inb  = lane < (int)a.kpw && b < a.B;
             const uint32_t pos  = t * a.B + b;         // position in keys/out (< 2^32 checked on host)
@@ -471,7 +452,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
             // Alg. 2: refresh the counter.  A plain store: the XCD's write-back L2 merges the many stores
             // a hot key draws (an agent-scope store per hit serialises them at the memory side and
             // triples the kernel time); they reach memory at the latest when the kernel ends.
-            if (tb.T && hit) tb.T[(uint64_t)set * W + (uint32_t)way] = tb.g;
+            if (tb.T && hit) tb.T[(uint64_t)set * W + (uint32_t)way] = g_call;
 
             if (kCoherent) {
                 __syncthreads();                           // rows were copied inside the retry loop
@@ -506,9 +487,8 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 }
                 o += c;
             }
-            if (lane == 0 && (uint32_t)(old >> 32) + 1u == a.n_tiles) {   // every tile has added its count
-                *a.n_miss = (uint32_t)old + total;
-                __hip_atomic_store(a.slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)(old >> 32) + 1u == a.n_tiles) {   // every tile has added its count (and read g)
+                finish_call(a, (uint32_t)old + total, lane);
             }
         }
         __syncthreads();                                // LDS lists are reused by the next tile
@@ -552,6 +532,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
         const uint32_t pos0 = t * a.B + lt * WPB * a.kpw;      // position of this tile's first key
         if (wave < WPB) {
             const Table   &tb   = a.tab[t];
+            const uint32_t g_call = tb.T ? *tb.gdev + 1u : 0u;               // as in query_kernel
             const uint32_t tid  = (uint32_t)wave * a.kpw + (uint32_t)lane;   // index in the tile (idle lanes alias, unused)
             const uint32_t b    = lt * WPB * a.kpw + tid;
             const bool     inb  = lane < (int)a.kpw && b < a.B;
@@ -584,7 +565,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
             const uint32_t rep = is_rep ? tid : (want ? h_own[my] : tid);
             const int way = probe_wave<W, kWave>(tb.K, key, set, is_rep);
             if (is_rep) r_slot[tid] = way >= 0 ? (uint64_t)set * W + (uint32_t)way : kMissed;
-            if (tb.T && is_rep && way >= 0) tb.T[(uint64_t)set * W + (uint32_t)way] = tb.g;
+            if (tb.T && is_rep && way >= 0) tb.T[(uint64_t)set * W + (uint32_t)way] = g_call;
             __syncthreads();                                    // #3 probe results visible
             const uint64_t res = want ? r_slot[rep] : kMissed;
             const bool hit = res != kMissed;
@@ -658,10 +639,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const Qu
                 }
                 o += c;
             }
-            if (lane == 0 && (uint32_t)(old >> 32) + 1u == a.n_tiles) {
-                *a.n_miss = (uint32_t)old + total;
-                __hip_atomic_store(a.slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            if ((uint32_t)(old >> 32) + 1u == a.n_tiles) finish_call(a, (uint32_t)old + total, lane);
         }
         __syncthreads();                                        // #5 LDS is reused by the next tile
     }
@@ -706,6 +684,7 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
     const uint32_t n_tiles = (n + KPW - 1) / KPW;
     const uint32_t wave_global = blockIdx.x * kWavesPerWg + wave;
     const uint32_t n_waves = gridDim.x * kWavesPerWg;
+    const uint32_t g_now = tb.T ? *tb.gdev : 0u;            // Alg. 3 stamps with the current iteration count
 
     for (uint32_t tile = wave_global; tile < n_tiles; tile += n_waves) {
         const uint32_t i = tile * KPW + lane;
@@ -740,7 +719,7 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
                 // without taking the word, instead of each occurrence owning the set in turn.
                 const int seen = probe_wave<W, KPW, true>(tb.K, key, set, pending);
                 if (pending && seen >= 0) {
-                    if (tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)seen, tb.g);     // Alg. 3: refresh
+                    if (tb.T) st_agent(tb.T + (uint64_t)set * W + (uint32_t)seen, g_now);    // Alg. 3: refresh
                     pending = false;
                 }
             }
@@ -767,13 +746,13 @@ __global__ void __launch_bounds__(kBlock) insert_kernel(const WriteArgs a) {
 #pragma unroll
                     for (int w = W - 1; w >= 0; --w) {
                         const int64_t kw = ld_agent(tb.K + (uint64_t)set * W + w);
-                        const uint32_t age = tb.g - ld_agent(tb.T + (uint64_t)set * W + w);
+                        const uint32_t age = g_now - ld_agent(tb.T + (uint64_t)set * W + w);
                         if (kw == kEmpty) empty_way = w;             // ends as the lowest empty way
                         if (w == W - 1 || age >= best) { best = age; oldest = w; }   // largest age, lowest way on ties
                     }
                     way = empty_way >= 0 ? empty_way : oldest;
                 }
-                if (own) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, tb.g);
+                if (own) st_agent(tb.T + (uint64_t)set * W + (uint32_t)way, g_now);
             } else if (fresh) {
                 way = (int)(c & (W - 1));                            // victim counter
             }
@@ -901,6 +880,8 @@ __global__ void __launch_bounds__(kBlock) update_kernel(const WriteArgs a) {
 }
 
 // ------------------------------------------------------------------ small kernels
+
+__global__ void set_u32_kernel(uint32_t *p, uint32_t v) { *p = v; }
 
 __global__ void fill_keys_kernel(int64_t *K, uint64_t n, int64_t v) {
     for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
@@ -1065,8 +1046,8 @@ struct hps_cache {
     std::atomic<int> query_dedup;
     int      policy;                      // HPS_POLICY_*
     uint32_t *T;                          // access stamps (LRU policy), else nullptr
-    std::atomic<uint32_t> g;              // global iteration count: one step per query call (LRU policy)
-    uint32_t *flags;                      // device word of HPS_FLAG_* bits
+    uint32_t *flags;                      // device words: [0] HPS_FLAG_* bits, [1] g, the global iteration
+                                          // count of Alg. 2 (one step per query call, LRU policy)
     int      n_cus;                       // compute units of the device
 };
 
@@ -1091,7 +1072,7 @@ Table table_of(const hps_cache *c) {
     t.smask = (c->S & (c->S - 1)) == 0 ? (uint32_t)(c->S - 1) : 0u;
     if (c->S == 1) t.smask = 0;           // S = 1: "h % 1" = 0 (a zero mask means "use modulo")
     t.T = c->T;
-    t.g = c->g.load(std::memory_order_relaxed);
+    t.gdev = c->flags + 1;
     t.flags = c->flags;
     return t;
 }
@@ -1120,20 +1101,10 @@ uint64_t *counter_word(hps_cache *c, void *stream) {
 // waves per work-group.  Chosen from the batch size (measured on 256 CUs with 512-byte rows):
 // small batches want many small work-groups, ~10^5 keys want 512-key tiles (half as many
 // same-address counter atomics, which cost ~11 ns each and serialise), large batches want
-// more loads in flight.  HPS_QUERY_SHAPE="KPW,U,WPB" in the environment overrides the choice
-// with another compiled shape (a tuning aid).
+// more loads in flight.
 struct QueryShape { int kpw, u, wpb; };
 
 QueryShape query_shape(uint64_t n) {
-    static const QueryShape forced = [] {
-        QueryShape q{0, 0, 0};
-        if (const char *e = std::getenv("HPS_QUERY_SHAPE")) {
-            int k = 0, u = 0, w = 0;
-            if (std::sscanf(e, "%d,%d,%d", &k, &u, &w) == 3) q = QueryShape{k, u, w};
-        }
-        return q;
-    }();
-    if (forced.kpw) return forced;
     if (n < (1u << 16)) return QueryShape{64, 4, 4};
     if (n < (1u << 18)) return QueryShape{64, 4, 8};
     return QueryShape{64, 8, 4};
@@ -1156,7 +1127,7 @@ hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, boo
         case 640404: launch_query_shape<W, 64, 4, 4>(a, coherent, dedup, st); break;
         case 640408: launch_query_shape<W, 64, 4, 8>(a, coherent, dedup, st); break;
         case 640804: launch_query_shape<W, 64, 8, 4>(a, coherent, dedup, st); break;
-        default: return fail(HPS_ERR_INVALID_ARG, "HPS_QUERY_SHAPE names a shape that is not compiled in");
+        default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
     }
     HIP_TRY(hipGetLastError());
     return HPS_OK;
@@ -1257,7 +1228,6 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->d = dim;
     c->K = nullptr; c->V = nullptr; c->sc = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr; c->word_half = 0;
     c->policy = policy;
-    c->g.store(0);
     c->concurrent_writers.store(1);
     c->query_dedup.store(0);
 
@@ -1269,8 +1239,8 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     if (e == hipSuccess) e = hipMalloc(&c->V, capacity * (size_t)dim * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&c->sc, c->S * 2 * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(&c->ring, 2 * kRing * sizeof(uint64_t));
-    if (e == hipSuccess) e = hipMalloc(&c->flags, sizeof(uint32_t));
-    if (e == hipSuccess) e = hipMemsetAsync(c->flags, 0, sizeof(uint32_t), 0);
+    if (e == hipSuccess) e = hipMalloc(&c->flags, 2 * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemsetAsync(c->flags, 0, 2 * sizeof(uint32_t), 0);
     if (e == hipSuccess && policy == HPS_POLICY_LRU) {
         e = hipMalloc(&c->T, capacity * sizeof(uint32_t));
         if (e == hipSuccess) e = hipMemsetAsync(c->T, 0, capacity * sizeof(uint32_t), 0);
@@ -1371,10 +1341,8 @@ static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, co
     }
     QueryArgs a;
     std::memset(&a, 0, sizeof(a));
-    for (uint32_t t = 0; t < n_tables; ++t) {
-        if (caches[t]->policy == HPS_POLICY_LRU) caches[t]->g.fetch_add(1, std::memory_order_relaxed);   // Alg. 2: g <- g + 1
-        a.tab[t] = table_of(caches[t]);
-    }
+    for (uint32_t t = 0; t < n_tables; ++t) a.tab[t] = table_of(caches[t]);
+    a.n_tables = n_tables;
     a.keys = keys;
     a.out = out;
     a.miss_idx = miss_idx;
@@ -1483,9 +1451,10 @@ hps_status_t hps_cache_export_lru(hps_cache_t *c, uint32_t *stamps, uint32_t *g,
     if (hps_status_t s = check_handle(c)) return s;
     if (c->policy != HPS_POLICY_LRU) return fail(HPS_ERR_INVALID_ARG, "the cache was not created with the LRU policy");
     if (!stamps || !g) return fail(HPS_ERR_INVALID_ARG, "stamps and g must not be NULL");
-    HIP_TRY(hipMemcpyAsync(stamps, c->T, c->S * c->W * sizeof(uint32_t), hipMemcpyDeviceToDevice,
-                           static_cast<hipStream_t>(stream)));
-    *g = c->g.load();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemcpyAsync(stamps, c->T, c->S * c->W * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipMemcpyAsync(g, c->flags + 1, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));                   // *g is a host word: it is valid on return
     return HPS_OK;
 }
 
@@ -1493,9 +1462,10 @@ hps_status_t hps_cache_import_lru(hps_cache_t *c, const uint32_t *stamps, uint32
     if (hps_status_t s = check_handle(c)) return s;
     if (c->policy != HPS_POLICY_LRU) return fail(HPS_ERR_INVALID_ARG, "the cache was not created with the LRU policy");
     if (!stamps) return fail(HPS_ERR_INVALID_ARG, "stamps must not be NULL");
-    HIP_TRY(hipMemcpyAsync(c->T, stamps, c->S * c->W * sizeof(uint32_t), hipMemcpyDeviceToDevice,
-                           static_cast<hipStream_t>(stream)));
-    c->g.store(g);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipMemcpyAsync(c->T, stamps, c->S * c->W * sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(set_u32_kernel, dim3(1), dim3(1), 0, st, c->flags + 1, g);
+    HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
 

@@ -20,6 +20,7 @@
 #include <string>
 
 #include "hps_dedup.h"
+#include "hps_mix.h"
 
 namespace {
 
@@ -48,16 +49,6 @@ hps_status_t fail(hps_status_t code, const std::string &msg) {
     } while (0)
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-
-// 64-bit finaliser of the splitmix64 generator (a bijection: distinct keys spread over all bits).
-__device__ __forceinline__ uint64_t mix64(uint64_t x) {
-    x ^= x >> 30;
-    x *= 0xBF58476D1CE4E5B9ull;
-    x ^= x >> 27;
-    x *= 0x94D049BB133111EBull;
-    x ^= x >> 31;
-    return x;
-}
 
 // The table has slots 0..mask for ordinary keys and slot mask + 1 for the key whose value is the
 // free-slot marker itself.
@@ -242,7 +233,8 @@ const char *hps_dedup_last_error(void) { return g_err.c_str(); }
 hps_status_t hps_dedup_create(size_t max_n, hps_dedup_t **out) {
     if (!out) return fail(HPS_ERR_INVALID_ARG, "out must not be NULL");
     *out = nullptr;
-    if (max_n == 0 || max_n >= (1ull << 31)) return fail(HPS_ERR_INVALID_ARG, "max_n must be in 1 .. 2^31 - 1");
+    // 2 * max_n slots must stay below 2^32: slot numbers, the mask and the extra slot behind the table are 32-bit
+    if (max_n == 0 || max_n > (1ull << 30)) return fail(HPS_ERR_INVALID_ARG, "max_n must be in 1 .. 2^30");
     hps_dedup_session *s = new (std::nothrow) hps_dedup_session();
     if (!s) return fail(HPS_ERR_OOM, "host allocation failed");
     s->magic = 0;

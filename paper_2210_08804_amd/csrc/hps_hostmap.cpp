@@ -10,21 +10,13 @@
 #include <vector>
 
 #include "hps_hostmap.h"
+#include "hps_mix.h"
 
 namespace {
 
 constexpr uint64_t kMagic = 0x4850534D41503031ull;
 constexpr size_t kSlabRows = 1 << 14;           // rows per allocation unit of a partition
 constexpr size_t kParallelFrom = 1024;          // batches at least this long are served by the helper threads too
-
-uint64_t mix64(uint64_t x) {
-    x ^= x >> 30;
-    x *= 0xBF58476D1CE4E5B9ull;
-    x ^= x >> 27;
-    x *= 0x94D049BB133111EBull;
-    x ^= x >> 31;
-    return x;
-}
 
 constexpr uint64_t kFree = ~0ull;                 // row number of an unused slot
 
@@ -69,9 +61,9 @@ struct Partition {
 // [n_part * t / n_thr, n_part * (t + 1) / n_thr).
 struct Job {
     const int64_t *keys = nullptr;
-    size_t n = 0;
     float *rows = nullptr;
-    const std::vector<uint32_t> *part = nullptr;
+    const std::vector<uint32_t> *order = nullptr;      // positions sorted by partition
+    const std::vector<size_t> *start = nullptr;        // [n_part + 1] first entry of each partition in `order`
     std::vector<size_t> absent;
 };
 
@@ -103,23 +95,21 @@ float *row_ptr(const hps_hostmap *m, const Partition &p, uint64_t r) {
     return p.slabs[r / kSlabRows] + (r % kSlabRows) * m->dim;
 }
 
-// Serve positions whose key lives in partitions [p0, p1): the positions of each partition are
-// gathered first so that its lock is taken once.
-size_t get_range(hps_hostmap *m, const int64_t *keys, size_t n, float *rows,
-                 const std::vector<uint32_t> &part, uint32_t p0, uint32_t p1) {
+// Serve positions whose key lives in partitions [p0, p1).  The positions have been bucketed by
+// partition once per batch (order / start), so every partition's lock is taken once and no
+// position is looked at by more than one thread.
+size_t get_range(hps_hostmap *m, const int64_t *keys, float *rows, const std::vector<uint32_t> &order,
+                 const std::vector<size_t> &start, uint32_t p0, uint32_t p1) {
     size_t absent = 0;
-    std::vector<size_t> mine;
     for (uint32_t p = p0; p < p1; ++p) {
-        mine.clear();
-        for (size_t i = 0; i < n; ++i)
-            if (part[i] == p) mine.push_back(i);
-        if (mine.empty()) continue;
+        const size_t b = start[p], e = start[p + 1];
+        if (b == e) continue;
         Partition &P = m->parts[p];
         std::lock_guard<std::mutex> lk(P.mu);
         const uint64_t mask = P.table.size() - 1;
-        for (size_t j = 0; j < mine.size(); ++j) {
-            if (j + 4 < mine.size()) __builtin_prefetch(&P.table[Partition::home(keys[mine[j + 4]], mask)]);
-            const size_t i = mine[j];
+        for (size_t j = b; j < e; ++j) {
+            if (j + 4 < e) __builtin_prefetch(&P.table[Partition::home(keys[order[j + 4]], mask)]);
+            const size_t i = order[j];
             const Slot &sl = P.table[P.find(keys[i])];
             if (sl.row == kFree) {
                 std::memset(rows + i * m->dim, 0, sizeof(float) * m->dim);
@@ -143,7 +133,7 @@ void helper_main(hps_hostmap *m, uint32_t t) {
         }
         const uint32_t p0 = (uint32_t)((uint64_t)m->n_part * t / m->n_thr);
         const uint32_t p1 = (uint32_t)((uint64_t)m->n_part * (t + 1) / m->n_thr);
-        m->job.absent[t] = get_range(m, m->job.keys, m->job.n, m->job.rows, *m->job.part, p0, p1);
+        m->job.absent[t] = get_range(m, m->job.keys, m->job.rows, *m->job.order, *m->job.start, p0, p1);
         {
             std::lock_guard<std::mutex> lk(m->pool_mu);
             if (--m->running == 0) m->done_cv.notify_one();
@@ -240,14 +230,26 @@ hps_status_t hps_hostmap_get(hps_hostmap_t *m, const int64_t *keys, size_t n, fl
     if (!keys || !rows) return HPS_ERR_INVALID_ARG;
     size_t absent = 0;
     try {
-        std::vector<uint32_t> part(n);
-        for (size_t i = 0; i < n; ++i) part[i] = part_of(m, keys[i]);
+        if (n >= (1ull << 32)) return HPS_ERR_INVALID_ARG;
+        // counting sort of the positions by partition: one pass to count, one to place
+        std::vector<uint8_t> part(n);                      // n_part <= 256
+        std::vector<size_t> start(m->n_part + 1, 0);
+        for (size_t i = 0; i < n; ++i) {
+            part[i] = (uint8_t)part_of(m, keys[i]);
+            ++start[part[i] + 1];
+        }
+        for (uint32_t p = 0; p < m->n_part; ++p) start[p + 1] += start[p];
+        std::vector<uint32_t> order(n);
+        {
+            std::vector<size_t> at(start.begin(), start.end() - 1);
+            for (size_t i = 0; i < n; ++i) order[at[part[i]]++] = (uint32_t)i;
+        }
         std::unique_lock<std::mutex> pool(m->job_mu, std::defer_lock);
         if (n >= kParallelFrom && m->n_thr > 1 && pool.try_lock()) {
             m->job.keys = keys;
-            m->job.n = n;
             m->job.rows = rows;
-            m->job.part = &part;
+            m->job.order = &order;
+            m->job.start = &start;
             {
                 std::lock_guard<std::mutex> lk(m->pool_mu);
                 m->running = m->n_thr - 1;
@@ -255,14 +257,14 @@ hps_status_t hps_hostmap_get(hps_hostmap_t *m, const int64_t *keys, size_t n, fl
             }
             m->pool_cv.notify_all();
             const uint32_t p1 = (uint32_t)((uint64_t)m->n_part * 1 / m->n_thr);
-            absent = get_range(m, keys, n, rows, part, 0, p1);               // the caller is thread 0
+            absent = get_range(m, keys, rows, order, start, 0, p1);           // the caller is thread 0
             {
                 std::unique_lock<std::mutex> lk(m->pool_mu);
                 m->done_cv.wait(lk, [&] { return m->running == 0; });
             }
             for (uint32_t t = 1; t < m->n_thr; ++t) absent += m->job.absent[t];
         } else {
-            absent = get_range(m, keys, n, rows, part, 0, m->n_part);
+            absent = get_range(m, keys, rows, order, start, 0, m->n_part);
         }
     } catch (const std::exception &) {
         return HPS_ERR_OOM;

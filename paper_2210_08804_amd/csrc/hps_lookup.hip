@@ -193,7 +193,7 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     uint32_t dim = 0;
     if (hps_cache_info(cache, nullptr, nullptr, &dim) != HPS_OK) return lfail(HPS_ERR_INVALID_ARG, "invalid cache handle");
     if (!fetch || !default_row) return lfail(HPS_ERR_INVALID_ARG, "fetch and default_row are required");
-    if (max_batch == 0 || max_batch >= (1ull << 31)) return lfail(HPS_ERR_INVALID_ARG, "max_batch must be in [1, 2^31)");
+    if (max_batch == 0 || max_batch > (1ull << 30)) return lfail(HPS_ERR_INVALID_ARG, "max_batch must be in [1, 2^30]");
     hps_lookup_session *L = new (std::nothrow) hps_lookup_session();
     if (!L) return lfail(HPS_ERR_OOM, "host allocation failed");
     L->cache = cache; L->max_batch = max_batch; L->dim = dim; L->threshold = hit_threshold;

@@ -134,3 +134,62 @@ def test_dedup_query_fill_insert_expand_as_one_graph():
         finally:
             torch.cuda.synchronize()
             B.hps_dedup_destroy(dd)
+
+
+def test_lru_iteration_count_advances_on_every_graph_replay():
+    """The paper's LRU rule under graph replay: query -> fetch of the missing rows -> insert,
+    captured once on an LRU cache.  The global iteration count g of Alg. 2 is a device word that
+    the query kernel advances, so every replay stamps with a new g; with a g frozen at capture
+    time all ages would tie and replacement would degenerate to 'lowest way'.  After every replay
+    the stamps, g, keys, counters and rows equal the oracle's (policy 1)."""
+    import test_gpu_lru as L
+    S, W, d, n = 512, 8, 16, 3000             # most sets fill and evict within the ten replays
+    with DeviceCache(S * W, W, d, concurrent_writers=False, policy=L.LRU) as gc:
+        oc = OracleCache(S * W, W, d, policy=L.LRU)
+        dk = torch.zeros(n, dtype=torch.int64, device="cuda")
+        out = torch.empty(n, d, dtype=torch.float32, device="cuda")
+        mrows = torch.empty(n, d, dtype=torch.float32, device="cuda")
+        mi = torch.empty(n, dtype=torch.int32, device="cuda")
+        mk = torch.empty(n, dtype=torch.int64, device="cuda")
+        nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+        g = torch.cuda.CUDAGraph()
+        cs = torch.cuda.Stream()
+        cs.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cs):
+            g.capture_begin()
+            B.hps_cache_query(gc.h, dk, n, out, mi, mk, nm, cs)
+            B.hps_backing_fetch(mk, n, d, version=0, rows=mrows, n_dev=nm, stream=cs)
+            B.hps_cache_insert_dn(gc.h, mk, mrows, n, nm, cs)
+            g.capture_end()
+        torch.cuda.synchronize()
+        n_exact = 0
+        for replay in range(10):
+            keys = inputs.zipf_keys(n, 20000, 1.05, 300 + replay)
+            dk.copy_(torch.from_numpy(keys))
+            out.view(torch.int32).fill_(SENTINEL)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            exp = np.full((n, d), SENTINEL, dtype=np.uint32)
+            _, omi, omk = oc.query(keys, exp)
+            assert oc.g == replay + 1
+            m = int(nm.item())
+            order = np.argsort(mi[:m].cpu().numpy().view(np.uint32))
+            assert m == len(omi) and (mi[:m].cpu().numpy().view(np.uint32)[order] == omi).all()
+            assert (mk[:m].cpu().numpy()[order] == omk).all()
+            assert (out.view(torch.int32).cpu().numpy().view(np.uint32) == exp).all()
+            exact = L.lru_insert_is_order_independent(oc, omk)
+            oc.insert(omk, L.rows_u32(omk, d))
+            if exact:
+                gk, gctr, gv, gt = L.assert_same(gc, oc)           # stamps and g included
+                n_exact += 1
+            else:
+                gk, gctr, gv = gc.export()
+                gt, gg = gc.export_lru()
+                assert gg == oc.g
+                check_state_invariants(gk, gctr, gv, oc.set_of)
+            oc.load_state(gk, gctr, gv, stamps=gt)
+            # stamps of this replay are the new g, not the g of capture time
+            assert gt.max() == replay + 1
+        assert n_exact >= 5, n_exact
+        assert (np.array(oc.ctr) > W).sum() > S // 2           # the LRU rule chose victims in most sets

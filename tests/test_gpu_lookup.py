@@ -1,5 +1,5 @@
 """Algorithm 1 (cache lookup with hit-rate-controlled synchronous or asynchronous insertion)
-through hps_lookup against the same procedure written out over the oracle cache.
+through hps_lookup against the oracle's statement of the same procedure (hpso_lookup).
 
 The lower tiers are a Python callback that returns the backing generator's rows.  After every
 asynchronous lookup the test drains the background queue, which makes the cache state after each
@@ -28,25 +28,13 @@ def make_fetch(d, log):
     return B.FETCH_FN(fetch)
 
 
-def unique_in_order(a):
-    _, first = np.unique(a, return_index=True)
-    return a[np.sort(first)]
-
-
 def reference_step(oc, keys, d, threshold, default_row):
-    """Alg. 1 over the oracle.  Returns (out, hit_rate, synchronous, keys to insert after the call)."""
-    n = len(keys)
-    out = np.zeros((n, d), dtype=np.uint32)
-    _, mi, mk = oc.query(keys, out)
-    rate = np.float32(1.0) - np.float32(len(mi)) / np.float32(n)
-    if len(mi) == 0:
-        return out, rate, False, None
-    uk = unique_in_order(mk)
-    if rate < np.float32(threshold):
-        out[mi] = inputs.backing_rows(mk, d, 0).view(np.uint32)
-        return out, rate, True, uk
-    out[mi] = default_row.view(np.uint32)
-    return out, rate, False, uk
+    """Alg. 1 on the oracle (oracle/hps_oracle.c: hpso_lookup, pinned by tests/test_oracle_lookup.py),
+    stopping before the insertion so that the test can classify the batch first.  Returns
+    (out, hit_rate, synchronous, distinct missing keys in first-occurrence order or None)."""
+    out, rate, sync, to_insert = oc.lookup(keys, inputs.backing_rows(keys, d, 0), threshold, default_row,
+                                           do_insert=False)
+    return out, rate, sync, (to_insert if len(to_insert) else None)
 
 
 @pytest.mark.parametrize("threshold", [0.0, 0.8, 2.0])

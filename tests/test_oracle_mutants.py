@@ -12,6 +12,7 @@ import oracle
 from oracle import hps_oracle
 
 import test_oracle_dedup as dedup_pins
+import test_oracle_lookup as lookup_pins
 import test_oracle_lru as lru_pins
 import test_oracle_pins as pins
 
@@ -47,6 +48,14 @@ MUTANTS = [
     ("dedup: place counted from one", "        inverse_out[i] = (uint32_t)j;", "        inverse_out[i] = (uint32_t)j + 1;"),
     ("dedup: a repeated key is listed again", "        if (j == u) unique_out[u++] = keys[i];", "        if (j == u || j == 0) unique_out[u++] = keys[i];"),
     ("expand: position used instead of the map", "memcpy(out + i * d, rows + (uint64_t)inverse[i] * d, sizeof(uint32_t) * d);", "memcpy(out + i * d, rows + (i < 37 ? i : 0) * d, sizeof(uint32_t) * d);"),
+    ("lookup: hit rate divides by the cache size", "float rate = 1.0f - (float)m / (float)n;", "float rate = 1.0f - (float)m / (float)(c->S * c->W);"),
+    ("lookup: a hit rate equal to the threshold counts as below it", "        if (rate < t) {", "        if (rate <= t) {"),
+    ("lookup: decision taken in double precision", "float rate = 1.0f - (float)m / (float)n;", "double rate = 1.0 - (double)m / (double)n;"),
+    ("lookup: default vector handed out in synchronous mode", "memcpy(out + (uint64_t)miss_idx[j] * c->d, lower + (uint64_t)miss_idx[j] * c->d,", "memcpy(out + (uint64_t)miss_idx[j] * c->d, default_row,"),
+    ("lookup: a repeated missing key is fetched again", "while (e < u && ins_keys[e] != miss_keys[j]) ++e;", "e = u;"),
+    ("lookup: fetched row taken by list index instead of position", "memcpy(ins_rows + u * c->d, lower + (uint64_t)miss_idx[j] * c->d,", "memcpy(ins_rows + u * c->d, lower + j * c->d,"),
+    ("lookup: nothing inserted in asynchronous mode", "if (do_insert) hpso_insert(c, ins_keys, ins_rows, u);", "if (do_insert && *synchronous) hpso_insert(c, ins_keys, ins_rows, u);"),
+    ("lookup: cached rows replaced by the lower tiers' rows", "    uint64_t m = hpso_query(c, keys, n, out, miss_idx, miss_keys);", "    uint64_t m = hpso_query(c, keys, n, out, miss_idx, miss_keys);\n    memcpy(out, lower, sizeof(uint32_t) * n * c->d);"),
     ("lru: new key not stamped", "            c->T[s * c->W + w] = c->g;\n        }\n        c->C[s] += 1;", "        }\n        c->C[s] += 1;"),
 ]
 
@@ -62,7 +71,7 @@ def build(tmp_path, name, text):
 def battery(lib, monkeypatch):
     """Runs the pins against `lib`; returns the name of the first pin that fails, or None."""
     cache = functools.partial(hps_oracle.OracleCache, lib=lib)
-    for mod in (pins, lru_pins):
+    for mod in (pins, lru_pins, lookup_pins):
         monkeypatch.setattr(mod, "OracleCache", cache)
     monkeypatch.setattr(pins, "mix64", functools.partial(hps_oracle.mix64, lib=lib))
     monkeypatch.setattr(oracle, "set_of", functools.partial(hps_oracle.set_of, lib=lib))
@@ -94,6 +103,10 @@ def battery(lib, monkeypatch):
         ("dedup vs set/dict/numpy", lambda: dedup_pins.test_against_set_dict_and_numpy_unique(1, 1.05)),
         ("dedup brute force", dedup_pins.test_brute_force_small_alphabets),
         ("expand is a gather", dedup_pins.test_expand_is_a_row_gather),
+        ("alg 1 worked batch", lookup_pins.test_worked_batch_at_and_above_the_threshold),
+        ("alg 1 degenerate batches", lookup_pins.test_degenerate_batches),
+        ("alg 1 single precision", lookup_pins.test_decision_is_taken_in_single_precision),
+        ("alg 1 over a dict", lambda: lookup_pins.test_against_alg1_over_a_dict(3, 0.6)),
     ]
     for name, fn in checks:
         try:
