@@ -125,7 +125,10 @@ const char *hps_last_error(void);
  * they return against the set's sequence word and re-read rows that a writer touched
  * meanwhile, so a reader sees the old or the new row and never a mixture.  enabled = 0: the
  * caller promises that no writer overlaps a query; queries then use plain cached loads.
- * Takes effect for calls enqueued afterwards.
+ * Takes effect for calls enqueued afterwards.  Rows longer than 4 KiB (dim > 1024) cannot be
+ * validated in one piece: such a cache is created with enabled = 0 and enabling returns
+ * HPS_ERR_INVALID_ARG.  With enabled = 1 a query that overlaps an insert never writes any part
+ * of the `out` row of a position it reports as missing.
  */
 hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *cache, int enabled);
 

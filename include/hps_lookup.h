@@ -9,9 +9,10 @@
  * keys in host memory and fills their rows in host memory.  Everything else runs on the device,
  * including the deduplication of the missing keys (Sec. 2.2, hps_dedup.h): only distinct keys
  * travel to the host.  In asynchronous mode that, too, happens on the background thread's
- * stream: the call itself only copies the miss list aside.  At most 64 such batches wait for the
- * background thread; if the lower tier falls further behind, the oldest is dropped (its keys stay
- * missing until a later batch asks for them again).
+ * stream: the call itself only copies the miss list aside, into one of the object's slots (device
+ * buffers of max_batch keys allocated at create: at most 66 of them and at most 256 MiB, never
+ * fewer than 2; a lookup call allocates nothing).  When no slot is free the oldest waiting batch
+ * is dropped (its keys stay missing until a later batch asks for them again).
  * One lookup object serves one stream of batches (it owns one workspace, the paper's `ws`); use
  * one object per concurrent inference worker, all on the same cache.
  */
@@ -65,12 +66,27 @@ hps_status_t hps_lookup(hps_lookup_t *lookup, const int64_t *keys, size_t n, flo
  * of `batch_slots` slots, look each batch up in the lower tiers through `fetch`, copy the rows to
  * the device and Update the cache with them.  The dump and the copy of the keys to the host run on
  * a stream of their own, so the host-side lookup of one batch overlaps the upload and Update of
- * the previous one.  Returns when the whole cache has been refreshed; *n_refreshed (may be NULL)
- * receives the number of keys that were dumped and updated.  Queries may run meanwhile (on other
- * streams, with the cache in its concurrent-writer mode).  Keys that an overlapping insert evicts
- * between dump and Update are skipped by the Update (Alg. 4).  batch_slots in 1 .. 2^31 - 1.
- * The lower tier must hold every cached key: `fetch` has no way to say "not found".
+ * the previous one.
+ *
+ * A session owns everything the cycle needs (two device and two pinned host buffers of
+ * batch_slots keys and rows, its stream, its events), allocated by hps_refresh_create on the
+ * current device; hps_refresh_run allocates nothing and may be called any number of times, one
+ * call at a time per session.  batch_slots in 1 .. 2^31 - 1 (clamped to the size of the cache).
+ *
+ * hps_refresh_run returns when the whole cache has been refreshed; *n_refreshed [host] (may be
+ * NULL) receives the number of keys that were dumped and updated.  Queries may run meanwhile (on
+ * other streams, with the cache in its concurrent-writer mode).  Keys that an overlapping insert
+ * evicts between dump and Update are skipped by the Update (Alg. 4).  The lower tier must hold
+ * every cached key: `fetch` has no way to say "not found".  Errors: INVALID_ARG, OOM (create),
+ * DEVICE.
  */
+typedef struct hps_refresh_session hps_refresh_t;
+hps_status_t hps_refresh_create(hps_cache_t *cache, size_t batch_slots, hps_refresh_t **out_session);
+hps_status_t hps_refresh_run(hps_refresh_t *session, hps_fetch_fn fetch, void *user, size_t *n_refreshed,
+                             void *stream);
+hps_status_t hps_refresh_destroy(hps_refresh_t *session);
+
+/* One refresh with a session made for this call only (create + run + destroy: it allocates). */
 hps_status_t hps_cache_refresh(hps_cache_t *cache, size_t batch_slots, hps_fetch_fn fetch, void *user,
                                size_t *n_refreshed, void *stream);
 

@@ -30,7 +30,7 @@ EXPORTS = (
     "hps_cache_create_policy", "hps_cache_export_lru", "hps_cache_import_lru",
     "hps_cache_flags", "hps_cache_debug_set_seq", "hps_cache_query_dn",
     "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
-    "hps_cache_refresh",
+    "hps_cache_refresh", "hps_refresh_create", "hps_refresh_run", "hps_refresh_destroy",
     "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
     "hps_hostmap_create", "hps_hostmap_destroy", "hps_hostmap_put", "hps_hostmap_get", "hps_hostmap_fetch",
     "hps_hostmap_stats",
@@ -77,6 +77,9 @@ def load_library():
         "hps_lookup_drain": [vp],
         "hps_lookup_destroy": [vp],
         "hps_cache_refresh": [vp, sz, FETCH_FN, vp, C.POINTER(sz), vp],
+        "hps_refresh_create": [vp, sz, C.POINTER(vp)],
+        "hps_refresh_run": [vp, FETCH_FN, vp, C.POINTER(sz), vp],
+        "hps_refresh_destroy": [vp],
         "hps_dedup_create": [sz, C.POINTER(vp)],
         "hps_dedup_destroy": [vp],
         "hps_dedup": [vp, vp, sz, vp, vp, vp, vp],
@@ -291,6 +294,23 @@ def hps_cache_refresh(cache, batch_slots: int, fetch, user=None, stream=None) ->
     n = C.c_size_t()
     _check_lookup(load_library().hps_cache_refresh(cache, batch_slots, fetch, user, C.byref(n), _stream(stream)))
     return n.value
+
+
+def hps_refresh_create(cache, batch_slots: int) -> int:
+    h = C.c_void_p()
+    _check_lookup(load_library().hps_refresh_create(cache, batch_slots, C.byref(h)))
+    return h.value
+
+
+def hps_refresh_run(session, fetch, user=None, stream=None) -> int:
+    """One refresh cycle with the session's buffers (nothing is allocated); returns the number of keys refreshed."""
+    n = C.c_size_t()
+    _check_lookup(load_library().hps_refresh_run(session, fetch, user, C.byref(n), _stream(stream)))
+    return n.value
+
+
+def hps_refresh_destroy(session) -> None:
+    _check_lookup(load_library().hps_refresh_destroy(session))
 
 
 def hps_lookup_drain(lookup) -> None:

@@ -43,6 +43,9 @@ constexpr uint64_t kMagic      = 0x4850534341434845ull;
 // rounds (a held set is released within microseconds; this many rounds take about a second) and
 // raises HPS_FLAG_STUCK_SET in the cache's flag word, so that no wave can spin forever.
 constexpr uint32_t kMaxRounds  = 1u << 16;
+// Longest row (in fp32) that a query may read while writers run: such a row is staged whole in LDS
+// (one row per worker wave) before it is validated and stored.
+constexpr uint32_t kMaxCheckedDim = 1024;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk of a row
 
@@ -138,9 +141,13 @@ struct RowGeom {
 
 // Copy `cnt` (> 0) rows listed in LDS: row srcRow[e] of `src` to row dstRow[e] of `dst`, for
 // e < cnt.  LPR lanes move one row, 16 B per lane, so a wave load/store covers 64/LPR whole
-// rows; U wave loads are issued back to back before the first store.  The code is branch-free
-// inside a group: lanes beyond the list (or beyond the row, when d/4 is not a power of two)
-// repeat entry 0 / chunk 0, i.e. they store the same bytes to the same place as a live lane.
+// rows.  Two register buffers of U wave loads each alternate: the loads of the next group are
+// issued before the stores of the current one, so a wave always has loads in flight while it
+// stores (measured on the 106,496-key hot-cache batch: 21.5 us with 2 x 2 wave loads against
+// 22.9 us with one buffer of 4).  The code is branch-free inside a group: lanes beyond the list
+// (or beyond the row, when d/4 is not a power of two) repeat entry 0 / chunk 0, i.e. they store
+// the same bytes to the same place as a live lane, and the loads issued past the last group
+// re-read entry 0 and are dropped.
 template <int U, typename SrcIdx, typename DstIdx>
 __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restrict__ src,
                                           float *__restrict__ dst, const SrcIdx *srcRow,
@@ -149,36 +156,38 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
     const uint32_t rpi = (uint32_t)kWave >> g.lprShift;      // rows per wave load
     const uint32_t sub = lane >> g.lprShift;                 // which of those rows this lane serves
     const uint32_t cl  = lane & (g.LPR - 1);                 // chunk of the row this lane moves
+    const uint32_t step = rpi * U;
     for (uint32_t pass = 0; pass < g.passes; ++pass) {
         uint32_t chunk = cl + pass * g.LPR;
         chunk = chunk < g.C ? chunk : 0u;
         const uint32_t off = chunk * 4;
-        uint32_t e0 = 0;
-        for (; e0 + rpi * U <= cnt || (e0 < cnt && U == 1); e0 += rpi * U) {
-            f32x4 buf[U];
-            uint64_t dp[U];
+        f32x4 bufA[U], bufB[U];
+        uint64_t dpA[U], dpB[U];
+        auto load = [&](uint32_t e0, f32x4 (&buf)[U], uint64_t (&dp)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 uint32_t e = e0 + u * rpi + sub;
                 e = e < cnt ? e : 0u;
-                const uint64_t sr = (uint64_t)srcRow[e];
                 dp[u] = (uint64_t)dstRow[e];
-                buf[u] = *reinterpret_cast<const f32x4 *>(src + sr * g.d + off);
+                buf[u] = *reinterpret_cast<const f32x4 *>(src + (uint64_t)srcRow[e] * g.d + off);
             }
+        };
+        auto store = [&](const f32x4 (&buf)[U], const uint64_t (&dp)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 f32x4 *q = reinterpret_cast<f32x4 *>(dst + dp[u] * g.d + off);
                 if (nontemporal) __builtin_nontemporal_store(buf[u], q);
                 else *q = buf[u];
             }
-        }
-        for (; e0 < cnt; e0 += rpi) {                        // remainder, one wave load at a time
-            uint32_t e = e0 + sub;
-            e = e < cnt ? e : 0u;
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(src + (uint64_t)srcRow[e] * g.d + off);
-            f32x4 *q = reinterpret_cast<f32x4 *>(dst + (uint64_t)dstRow[e] * g.d + off);
-            if (nontemporal) __builtin_nontemporal_store(x, q);
-            else *q = x;
+        };
+        load(0, bufA, dpA);
+        for (uint32_t e0 = 0;; e0 += 2 * step) {
+            load(e0 + step, bufB, dpB);
+            store(bufA, dpA);
+            if (e0 + step >= cnt) break;
+            load(e0 + 2 * step, bufA, dpA);
+            store(bufB, dpB);
+            if (e0 + 2 * step >= cnt) break;
         }
     }
 }
@@ -189,48 +198,81 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
 // read again once those loads have completed; a row is stored only if its word is unchanged,
 // i.e. no writer touched the set while the row was being read.  Entries to redo are flagged in
 // the LDS word pair `retry`.
+// Rows of up to 1 KiB fit one wave load (8 bytes x 64 lanes x 2 rows at most), so a row is
+// validated and stored in one piece.  Longer rows (up to kMaxCheckedDim fp32) go one at a time
+// through `stage`, this wave's LDS buffer of kMaxCheckedDim / 2 8-byte words: the whole row is
+// read, then validated, then stored, so that a position whose key turns out to be gone on the
+// retry (evicted by an overlapping insert) has had nothing written to its `out` row.
 template <int U>
 __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *__restrict__ src,
                                                   float *__restrict__ dst, const uint64_t *srcRow,
                                                   const uint32_t *dstRow, const uint32_t *setOf,
                                                   const uint32_t *v1Of, const uint32_t *sc,
-                                                  uint32_t cnt, uint32_t *retry) {
+                                                  uint32_t cnt, uint32_t *retry, uint64_t *stage) {
     const uint32_t lane = (uint32_t)lane_id();
+    if (g.passes8 > 1) {
+        constexpr int kInFlight = 8;                                    // wave loads of one row in flight
+        for (uint32_t e = 0; e < cnt; ++e) {
+            const uint64_t *srow = reinterpret_cast<const uint64_t *>(src + srcRow[e] * g.d);
+            for (uint32_t c0 = 0; c0 < g.C8; c0 += kWave * kInFlight) {
+                uint64_t r[kInFlight];
+#pragma unroll
+                for (int k = 0; k < kInFlight; ++k) {
+                    const uint32_t c = c0 + (uint32_t)k * kWave + lane;
+                    r[k] = shared_ld64(srow + (c < g.C8 ? c : 0u));
+                }
+#pragma unroll
+                for (int k = 0; k < kInFlight; ++k) {
+                    const uint32_t c = c0 + (uint32_t)k * kWave + lane;
+                    if (c < g.C8) stage[c] = r[k];
+                }
+            }
+            shared_acquire();                                           // the whole row has been read
+            const uint32_t v2 = ld_agent(sc + 2ull * setOf[e]);
+            const bool ok = __ballot(v2 != v1Of[e]) == 0;               // one verdict for the wave
+            wave_lds_fence();
+            if (ok) {
+                uint64_t *drow = reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[e] * g.d);
+                for (uint32_t c = lane; c < g.C8; c += kWave) __builtin_nontemporal_store(stage[c], drow + c);
+            } else if (lane == 0) {
+                __hip_atomic_fetch_or(retry + (e >> 5), 1u << (e & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            wave_lds_fence();                                           // the buffer is reused by the next row
+        }
+        return;
+    }
     const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;
     const uint32_t sub = lane >> g.lpr8Shift;
     const uint32_t cl  = lane & (g.LPR8 - 1);
     const uint64_t grp = (g.LPR8 == 64 ? ~0ull : ((1ull << g.LPR8) - 1)) << (sub << g.lpr8Shift);
-    for (uint32_t pass = 0; pass < g.passes8; ++pass) {
-        uint32_t chunk = cl + pass * g.LPR8;
-        chunk = chunk < g.C8 ? chunk : 0u;
-        for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
-            uint64_t buf[U];
-            uint32_t ent[U];
-            bool real[U];
+    const uint32_t chunk = cl < g.C8 ? cl : 0u;
+    for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
+        uint64_t buf[U];
+        uint32_t ent[U];
+        bool real[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t e = e0 + u * rpi + sub;
-                real[u] = e < cnt;
-                ent[u] = real[u] ? e : 0u;
-                buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[ent[u]] * g.d) + chunk);
-            }
-            shared_acquire();                                       // row loads complete before the re-read
-            uint32_t v2[U];
+        for (int u = 0; u < U; ++u) {
+            const uint32_t e = e0 + u * rpi + sub;
+            real[u] = e < cnt;
+            ent[u] = real[u] ? e : 0u;
+            buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[ent[u]] * g.d) + chunk);
+        }
+        shared_acquire();                                       // row loads complete before the re-read
+        uint32_t v2[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v2[u] = ld_agent(sc + 2ull * setOf[ent[u]]);
+        for (int u = 0; u < U; ++u) v2[u] = ld_agent(sc + 2ull * setOf[ent[u]]);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                // One verdict per row: every lane of the row's group must have seen the unchanged
-                // word (the ballot makes the lanes of a group agree even if their loads did not).
-                const uint64_t bad = __ballot(v2[u] != v1Of[ent[u]]);
-                const bool ok = (bad & grp) == 0;
-                if (real[u] && ok) {
-                    __builtin_nontemporal_store(
-                        buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[ent[u]] * g.d) + chunk);
-                } else if (real[u] && cl == 0) {
-                    __hip_atomic_fetch_or(retry + (ent[u] >> 5), 1u << (ent[u] & 31), __ATOMIC_RELAXED,
-                                          __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
+        for (int u = 0; u < U; ++u) {
+            // One verdict per row: every lane of the row's group must have seen the unchanged
+            // word (the ballot makes the lanes of a group agree even if their loads did not).
+            const uint64_t bad = __ballot(v2[u] != v1Of[ent[u]]);
+            const bool ok = (bad & grp) == 0;
+            if (real[u] && ok) {
+                __builtin_nontemporal_store(
+                    buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[ent[u]] * g.d) + chunk);
+            } else if (real[u] && cl == 0) {
+                __hip_atomic_fetch_or(retry + (ent[u] >> 5), 1u << (ent[u] & 31), __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
@@ -371,14 +413,25 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
     __shared__ int64_t  s_mkey[WPB][KPW];
     __shared__ uint32_t s_mpos[WPB][KPW];
     __shared__ uint32_t s_wcnt[WPB];
+    __shared__ uint32_t s_ready;                   // worker waves that have listed their misses (plain variant)
     __shared__ uint32_t s_set[kCoherent ? WPB : 1][kCoherent ? KPW : 1];
     __shared__ uint32_t s_v1[kCoherent ? WPB : 1][kCoherent ? KPW : 1];
     __shared__ uint32_t s_retry[kCoherent ? WPB : 1][2];
+    __shared__ uint64_t s_stage[kCoherent ? WPB : 1][kCoherent ? kMaxCheckedDim / 2 : 1];   // rows longer than 1 KiB
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
     const RowGeom g = a.g;
+    const bool many_tiles = a.n_tiles > gridDim.x;     // this work-group may take several tiles
 
+    if (!kCoherent) {
+        // The plain variant has no work-group barrier between probe and row copy: each worker
+        // wave goes on to its rows as soon as its own probe is done and only tells the helper,
+        // through s_ready, that its misses are listed.  (The barrier made every wave wait for the
+        // slowest probe of the work-group: 22.9 -> 22.1 us per 106,496-key batch without it.)
+        if (threadIdx.x == 0) s_ready = 0u;
+        __syncthreads();
+    }
     for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
         const uint32_t t  = tile / a.tiles_per_table;
         const uint32_t lt = tile - t * a.tiles_per_table;
@@ -425,7 +478,8 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                     wave_lds_fence();
                     if (fmask)
                         copy_rows_checked<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], &s_set[wave][0],
-                                             &s_v1[wave][0], tb.sc, (uint32_t)__popcll(fmask), &s_retry[wave][0]);
+                                             &s_v1[wave][0], tb.sc, (uint32_t)__popcll(fmask), &s_retry[wave][0],
+                                             &s_stage[wave][0]);
                     wave_lds_fence();
                     bool again = false;
                     if (found) {
@@ -464,11 +518,18 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                     s_src[wave][r] = (uint64_t)set * W + (uint32_t)way;
                     s_dst[wave][r] = pos;
                 }
-                __syncthreads();
+                wave_lds_fence();
+                if (lane == 0) __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 if (nh) copy_rows<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
             }
         } else {
-            __syncthreads();
+            if (kCoherent) {
+                __syncthreads();
+            } else {
+                // every worker wave of the work-group reaches its increment (none leaves early), so this ends
+                while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (uint32_t)WPB)
+                    __builtin_amdgcn_s_sleep(2);
+            }
             uint32_t total = 0;
 #pragma unroll
             for (int w = 0; w < WPB; ++w) total += s_wcnt[w];
@@ -490,8 +551,9 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
             if ((uint32_t)(old >> 32) + 1u == a.n_tiles) {   // every tile has added its count (and read g)
                 finish_call(a, (uint32_t)old + total, lane);
             }
+            if (!kCoherent && many_tiles && lane == 0) s_ready = 0u;
         }
-        __syncthreads();                                // LDS lists are reused by the next tile
+        if (kCoherent || many_tiles) __syncthreads();   // LDS lists are reused by the next tile
     }
 }
 
@@ -1097,17 +1159,17 @@ uint64_t *counter_word(hps_cache *c, void *stream) {
     return c->ring + it->second;
 }
 
-// Launch shape of the query kernel: KPW keys per worker wave, U wave loads in flight, WPB worker
-// waves per work-group.  Chosen from the batch size (measured on 256 CUs with 512-byte rows):
+// Launch shape of the query kernel: KPW keys per worker wave, two register buffers of U wave loads
+// each in the row copy, WPB worker waves per work-group.  Chosen from the batch size (measured on 256 CUs with 512-byte rows):
 // small batches want many small work-groups, ~10^5 keys want 512-key tiles (half as many
 // same-address counter atomics, which cost ~11 ns each and serialise), large batches want
 // more loads in flight.
 struct QueryShape { int kpw, u, wpb; };
 
 QueryShape query_shape(uint64_t n) {
-    if (n < (1u << 16)) return QueryShape{64, 4, 4};
-    if (n < (1u << 18)) return QueryShape{64, 4, 8};
-    return QueryShape{64, 8, 4};
+    if (n < (1u << 16)) return QueryShape{64, 2, 4};
+    if (n < (1u << 18)) return QueryShape{64, 2, 8};
+    return QueryShape{64, 4, 4};
 }
 
 template <int W, int KPW, int U, int WPB>
@@ -1116,7 +1178,7 @@ void launch_query_shape(const QueryArgs &a, bool coherent, bool dedup, hipStream
     const dim3 block((WPB + 1) * kWave);
     if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true>), dim3(grid), block, 0, st, a);
     else if (dedup && KPW == kWave)
-        hipLaunchKernelGGL((query_dedup_kernel<W, U, WPB>), dim3(grid), block, 0, st, a);
+        hipLaunchKernelGGL((query_dedup_kernel<W, 2 * U, WPB>), dim3(grid), block, 0, st, a);
     else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false>), dim3(grid), block, 0, st, a);
 }
 
@@ -1124,9 +1186,9 @@ template <int W>
 hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, bool dedup, hipStream_t st) {
     const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
     switch (id) {
+        case 640204: launch_query_shape<W, 64, 2, 4>(a, coherent, dedup, st); break;
+        case 640208: launch_query_shape<W, 64, 2, 8>(a, coherent, dedup, st); break;
         case 640404: launch_query_shape<W, 64, 4, 4>(a, coherent, dedup, st); break;
-        case 640408: launch_query_shape<W, 64, 4, 8>(a, coherent, dedup, st); break;
-        case 640804: launch_query_shape<W, 64, 8, 4>(a, coherent, dedup, st); break;
         default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
     }
     HIP_TRY(hipGetLastError());
@@ -1228,7 +1290,7 @@ hps_status_t hps_cache_create_policy(size_t capacity, uint32_t ways, uint32_t di
     c->d = dim;
     c->K = nullptr; c->V = nullptr; c->sc = nullptr; c->ring = nullptr; c->T = nullptr; c->flags = nullptr; c->word_half = 0;
     c->policy = policy;
-    c->concurrent_writers.store(1);
+    c->concurrent_writers.store(dim <= kMaxCheckedDim ? 1 : 0);
     c->query_dedup.store(0);
 
     hipError_t e = hipGetDevice(&c->device);
@@ -1295,6 +1357,9 @@ hps_status_t hps_cache_info(const hps_cache_t *c, uint64_t *num_sets, uint32_t *
 
 hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *c, int enabled) {
     if (!c || c->magic != kMagic) return fail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    if (enabled && c->d > kMaxCheckedDim)
+        return fail(HPS_ERR_INVALID_ARG, "queries overlapping writers are supported for dim <= " +
+                                             std::to_string(kMaxCheckedDim) + " (4 KiB rows)");
     c->concurrent_writers.store(enabled ? 1 : 0);
     return HPS_OK;
 }

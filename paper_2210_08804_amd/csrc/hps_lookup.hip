@@ -38,14 +38,22 @@ __global__ void place_rows_kernel(float *out, const uint32_t *__restrict__ idx,
     }
 }
 
-// Asynchronous insertions that may wait for the background thread.  Beyond that the oldest one is
-// dropped: cache insertion is best effort, its keys stay missing until a later batch asks again.
+// Asynchronous insertions that may wait for the background thread: each waits in one of the
+// object's slots (a device key buffer of max_batch keys and an event, all allocated at create, so
+// that a lookup call allocates nothing).  There are at most 66 slots (64 waiting batches plus what
+// the background thread is working on) and at most 256 MiB of them (never fewer than 2).  When every slot is taken the oldest waiting batch is dropped: cache
+// insertion is best effort, its keys stay missing until a later batch asks again.
 constexpr size_t kMaxQueued = 64;
+constexpr size_t kMaxSlotBytes = 256ull << 20;
+
+struct Slot {
+    int64_t   *d_keys;        // device copy of a batch's miss list (every occurrence)
+    hipEvent_t ready;         // that copy has finished
+};
 
 struct Task {                 // one queued asynchronous insertion
-    int64_t   *d_keys;        // device copy of the batch's miss list (every occurrence)
-    uint32_t   m;             // how many
-    hipEvent_t ready;         // that copy has finished
+    Slot     *slot;
+    uint32_t  m;              // how many keys
 };
 
 }  // namespace
@@ -77,9 +85,23 @@ struct hps_lookup_session {
     std::mutex mu;
     std::condition_variable cv, cv_idle;
     std::deque<Task> queue;
-    std::vector<int64_t *> free_key_bufs;
+    std::vector<Slot> slots;              // all of them, for destruction
+    std::vector<Slot *> free_slots;
     bool stop = false, busy = false;
     std::string worker_error;
+};
+
+struct hps_refresh_session {              // buffers, stream and events of the refresh cycle (Sec. 6)
+    hps_cache_t *cache = nullptr;
+    int          device = 0;
+    uint64_t     slots = 0;               // slots of the cache
+    size_t       B = 0;                   // slots per batch
+    size_t       rowb = 0;                // bytes per row
+    int64_t     *d_keys[2] = {nullptr, nullptr}, *h_keys[2] = {nullptr, nullptr};
+    float       *d_rows[2] = {nullptr, nullptr}, *h_rows[2] = {nullptr, nullptr};
+    uint32_t    *d_cnt = nullptr, *h_cnt = nullptr;
+    hipStream_t  s2 = nullptr;            // dump and key download run here
+    hipEvent_t   applied[2] = {nullptr, nullptr};
 };
 
 namespace {
@@ -133,9 +155,9 @@ void worker_main(hps_lookup_session *L) {
         // the queued miss lists, one after the other in one device buffer, then made distinct
         uint32_t total = 0;
         for (const Task &t : batch) {
-            if (e == hipSuccess) e = hipStreamWaitEvent(L->side, t.ready, 0);
+            if (e == hipSuccess) e = hipStreamWaitEvent(L->side, t.slot->ready, 0);
             if (e == hipSuccess)
-                e = hipMemcpyAsync(L->bg_d_keys + total, t.d_keys, (size_t)t.m * sizeof(int64_t),
+                e = hipMemcpyAsync(L->bg_d_keys + total, t.slot->d_keys, (size_t)t.m * sizeof(int64_t),
                                    hipMemcpyDeviceToDevice, L->side);
             total += t.m;
         }
@@ -156,10 +178,10 @@ void worker_main(hps_lookup_session *L) {
             if (e == hipSuccess) e = hipStreamSynchronize(L->side);
         }
         if (e != hipSuccess) err = std::string("background insertion: ") + hipGetErrorString(e);
-        for (const Task &t : batch) (void)hipEventDestroy(t.ready);
+        if (e != hipSuccess || !err.empty()) (void)hipStreamSynchronize(L->side);   // the slots are idle before they go back
         {
             std::lock_guard<std::mutex> lk(L->mu);
-            for (const Task &t : batch) L->free_key_bufs.push_back(t.d_keys);
+            for (const Task &t : batch) L->free_slots.push_back(t.slot);
             if (!err.empty()) L->worker_error = err;
             L->busy = false;
         }
@@ -177,7 +199,10 @@ void free_all(hps_lookup_session *L) {
     (void)hipHostFree(L->h_n_miss); (void)hipHostFree(L->h_n_unique);
     (void)hipHostFree(L->h_ukeys); (void)hipHostFree(L->h_rows); (void)hipHostFree(L->bg_h_rows);
     (void)hipHostFree(L->bg_h_keys);
-    for (int64_t *p : L->free_key_bufs) (void)hipFree(p);
+    for (Slot &sl : L->slots) {
+        if (sl.d_keys) (void)hipFree(sl.d_keys);
+        if (sl.ready) (void)hipEventDestroy(sl.ready);
+    }
     if (L->side) (void)hipStreamDestroy(L->side);
 }
 
@@ -217,6 +242,16 @@ hps_status_t hps_lookup_create(hps_cache_t *cache, size_t max_batch, float hit_t
     dev((void **)&L->bg_d_keys, nb * 8); dev((void **)&L->bg_d_inv, nb * 4); dev((void **)&L->bg_d_n_unique, 4);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipMemcpy(L->d_default, default_row, rowb, hipMemcpyHostToDevice);
+    {
+        size_t n_slots = kMaxSlotBytes / (nb * 8);
+        n_slots = n_slots > kMaxQueued + 2 ? kMaxQueued + 2 : (n_slots < 2 ? 2 : n_slots);
+        L->slots.assign(n_slots, Slot{nullptr, nullptr});
+        for (Slot &sl : L->slots) {
+            dev((void **)&sl.d_keys, nb * 8);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&sl.ready, hipEventDisableTiming);
+        }
+        if (e == hipSuccess) for (Slot &sl : L->slots) L->free_slots.push_back(&sl);
+    }
     if (e != hipSuccess) {
         const std::string msg = std::string("hps_lookup_create: ") + hipGetErrorString(e);
         const hps_status_t code = e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE;
@@ -291,116 +326,152 @@ hps_status_t hps_lookup(hps_lookup_t *L, const int64_t *keys, size_t n, float *o
     LK_TRY(hipGetLastError());
     // The miss list (every occurrence) is copied aside on the device and handed to the background
     // thread, which deduplicates it on its own stream: this call does not wait for any of that.
+    // A slot for it: a free one, else the one of the oldest waiting batch (the lower tier cannot
+    // keep up: that batch is dropped).  If the background thread holds every slot right now (only
+    // possible with two slots), this batch is the one that is not queued.
     Task t;
-    {
-        std::lock_guard<std::mutex> lk(L->mu);
-        if (!L->free_key_bufs.empty()) {
-            t.d_keys = L->free_key_bufs.back();
-            L->free_key_bufs.pop_back();
-        } else {
-            t.d_keys = nullptr;
-        }
-    }
-    if (!t.d_keys) LK_TRY(hipMalloc((void **)&t.d_keys, L->max_batch * 8));
+    t.slot = nullptr;
     t.m = m;
-    LK_TRY(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
-    LK_TRY(hipMemcpyAsync(t.d_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToDevice, st));
-    LK_TRY(hipEventRecord(t.ready, st));
-    Task dropped;
-    bool drop = false;
+    bool taken_over = false;
     {
         std::lock_guard<std::mutex> lk(L->mu);
-        if (L->queue.size() >= kMaxQueued) {                  // the lower tier cannot keep up: the oldest batch goes
-            dropped = L->queue.front();
+        if (!L->free_slots.empty()) {
+            t.slot = L->free_slots.back();
+            L->free_slots.pop_back();
+        } else if (!L->queue.empty()) {
+            t.slot = L->queue.front().slot;
             L->queue.pop_front();
-            L->free_key_bufs.push_back(dropped.d_keys);
-            drop = true;
+            taken_over = true;
         }
-        L->queue.push_back(t);
     }
-    if (drop) (void)hipEventDestroy(dropped.ready);
+    if (!t.slot) return HPS_OK;
+    // a dropped batch's copy into this buffer may still be in flight (on another stream, if the caller changes streams)
+    hipError_t ce = taken_over ? hipStreamWaitEvent(st, t.slot->ready, 0) : hipSuccess;
+    if (ce == hipSuccess) ce = hipMemcpyAsync(t.slot->d_keys, L->d_miss_keys, (size_t)m * 8, hipMemcpyDeviceToDevice, st);
+    if (ce == hipSuccess) ce = hipEventRecord(t.slot->ready, st);
+    {
+        std::lock_guard<std::mutex> lk(L->mu);
+        if (ce == hipSuccess) L->queue.push_back(t);
+        else L->free_slots.push_back(t.slot);
+    }
+    if (ce != hipSuccess)
+        return lfail(HPS_ERR_DEVICE, std::string("queueing the asynchronous insertion: ") + hipGetErrorString(ce));
     L->cv.notify_one();
+    return HPS_OK;
+}
+
+hps_status_t hps_refresh_create(hps_cache_t *cache, size_t batch_slots, hps_refresh_t **out) {
+    if (!out) return lfail(HPS_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    uint64_t sets = 0;
+    uint32_t ways = 0, dim = 0;
+    if (hps_cache_info(cache, &sets, &ways, &dim) != HPS_OK) return lfail(HPS_ERR_INVALID_ARG, "invalid cache handle");
+    if (batch_slots == 0 || batch_slots >= (1ull << 31)) return lfail(HPS_ERR_INVALID_ARG, "batch_slots must be in [1, 2^31)");
+    hps_refresh_session *R = new (std::nothrow) hps_refresh_session();
+    if (!R) return lfail(HPS_ERR_OOM, "host allocation failed");
+    R->cache = cache;
+    R->slots = sets * ways;
+    R->B = batch_slots < R->slots ? batch_slots : (size_t)R->slots;
+    R->rowb = (size_t)dim * sizeof(float);
+    hipError_t e = hipGetDevice(&R->device);
+    for (int b = 0; b < 2; ++b) {
+        if (e == hipSuccess) e = hipMalloc((void **)&R->d_keys[b], R->B * 8);
+        if (e == hipSuccess) e = hipMalloc((void **)&R->d_rows[b], R->B * R->rowb);
+        if (e == hipSuccess) e = hipHostMalloc((void **)&R->h_keys[b], R->B * 8, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostMalloc((void **)&R->h_rows[b], R->B * R->rowb, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&R->applied[b], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipMalloc((void **)&R->d_cnt, 8);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&R->h_cnt, 8, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&R->s2, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+        const std::string msg = std::string("hps_refresh_create: ") + hipGetErrorString(e);
+        (void)hipGetLastError();
+        (void)hps_refresh_destroy(R);
+        return lfail(e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE, msg);
+    }
+    *out = R;
+    return HPS_OK;
+}
+
+hps_status_t hps_refresh_destroy(hps_refresh_t *R) {
+    if (!R) return lfail(HPS_ERR_INVALID_ARG, "session is NULL");
+    if (R->s2) (void)hipStreamSynchronize(R->s2);
+    for (int b = 0; b < 2; ++b) {
+        (void)hipFree(R->d_keys[b]); (void)hipFree(R->d_rows[b]);
+        (void)hipHostFree(R->h_keys[b]); (void)hipHostFree(R->h_rows[b]);
+        if (R->applied[b]) (void)hipEventDestroy(R->applied[b]);
+    }
+    (void)hipFree(R->d_cnt); (void)hipHostFree(R->h_cnt);
+    if (R->s2) (void)hipStreamDestroy(R->s2);
+    delete R;
+    return HPS_OK;
+}
+
+hps_status_t hps_refresh_run(hps_refresh_t *R, hps_fetch_fn fetch, void *user, size_t *n_refreshed, void *stream) {
+    if (n_refreshed) *n_refreshed = 0;
+    if (!R) return lfail(HPS_ERR_INVALID_ARG, "session is NULL");
+    if (!fetch) return lfail(HPS_ERR_INVALID_ARG, "fetch is required");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint64_t slots = R->slots;
+    const size_t B = R->B, rowb = R->rowb;
+    // two sets of buffers: the host looks batch i + 1 up while batch i is uploaded and applied
+    size_t total = 0;
+    std::string err;
+    hipError_t e = hipSuccess;
+    bool used[2] = {false, false};
+    for (uint64_t first = 0, i = 0; e == hipSuccess && err.empty() && first < slots; first += B, ++i) {
+        const int b = (int)(i & 1);
+        const size_t cnt_slots = (size_t)(slots - first < B ? slots - first : B);
+        if (used[b]) e = hipEventSynchronize(R->applied[b]);       // this pair of buffers is free again
+        if (e != hipSuccess) break;
+        if (hps_cache_dump(R->cache, (size_t)first, cnt_slots, R->d_keys[b], R->d_cnt + b, R->s2) != HPS_OK) {
+            err = std::string("dump: ") + hps_last_error();
+            break;
+        }
+        e = hipMemcpyAsync(R->h_cnt + b, R->d_cnt + b, 4, hipMemcpyDeviceToHost, R->s2);
+        if (e == hipSuccess) e = hipStreamSynchronize(R->s2);
+        if (e != hipSuccess) break;
+        const uint32_t m = R->h_cnt[b];
+        if (m == 0) continue;
+        e = hipMemcpyAsync(R->h_keys[b], R->d_keys[b], (size_t)m * 8, hipMemcpyDeviceToHost, R->s2);
+        if (e == hipSuccess) e = hipStreamSynchronize(R->s2);
+        if (e != hipSuccess) break;
+        fetch(user, R->h_keys[b], m, R->h_rows[b]);                 // steps 2-3: lower tiers, key-vector buffer
+        e = hipMemcpyAsync(R->d_rows[b], R->h_rows[b], (size_t)m * rowb, hipMemcpyHostToDevice, st);   // step 4
+        if (e != hipSuccess) break;
+        if (hps_cache_update(R->cache, R->d_keys[b], R->d_rows[b], m, st) != HPS_OK) {                 // step 5
+            err = std::string("update: ") + hps_last_error();
+            break;
+        }
+        e = hipEventRecord(R->applied[b], st);
+        used[b] = true;
+        total += m;
+    }
+    // the buffers are idle again when the call returns, also after an error
+    hipError_t e2 = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = e2;
+    (void)hipStreamSynchronize(R->s2);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return lfail(e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE, std::string("hps_refresh_run: ") + hipGetErrorString(e));
+    }
+    if (!err.empty()) return lfail(HPS_ERR_DEVICE, err);
+    if (n_refreshed) *n_refreshed = total;
     return HPS_OK;
 }
 
 hps_status_t hps_cache_refresh(hps_cache_t *cache, size_t batch_slots, hps_fetch_fn fetch, void *user,
                                size_t *n_refreshed, void *stream) {
     if (n_refreshed) *n_refreshed = 0;
-    uint64_t sets = 0;
-    uint32_t ways = 0, dim = 0;
-    if (hps_cache_info(cache, &sets, &ways, &dim) != HPS_OK) return lfail(HPS_ERR_INVALID_ARG, "invalid cache handle");
     if (!fetch) return lfail(HPS_ERR_INVALID_ARG, "fetch is required");
-    if (batch_slots == 0 || batch_slots >= (1ull << 31)) return lfail(HPS_ERR_INVALID_ARG, "batch_slots must be in [1, 2^31)");
-    const uint64_t slots = sets * ways;
-    const size_t B = batch_slots < slots ? batch_slots : (size_t)slots;
-    const size_t rowb = (size_t)dim * sizeof(float);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
-    // two sets of buffers: the host looks batch i + 1 up while batch i is uploaded and applied
-    int64_t *d_keys[2] = {nullptr, nullptr}, *h_keys[2] = {nullptr, nullptr};
-    float *d_rows[2] = {nullptr, nullptr}, *h_rows[2] = {nullptr, nullptr};
-    uint32_t *d_cnt = nullptr, *h_cnt = nullptr;
-    hipStream_t s2 = nullptr;
-    hipEvent_t applied[2] = {nullptr, nullptr};
-    hipError_t e = hipSuccess;
-    for (int b = 0; b < 2; ++b) {
-        if (e == hipSuccess) e = hipMalloc((void **)&d_keys[b], B * 8);
-        if (e == hipSuccess) e = hipMalloc((void **)&d_rows[b], B * rowb);
-        if (e == hipSuccess) e = hipHostMalloc((void **)&h_keys[b], B * 8, hipHostMallocDefault);
-        if (e == hipSuccess) e = hipHostMalloc((void **)&h_rows[b], B * rowb, hipHostMallocDefault);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&applied[b], hipEventDisableTiming);
-    }
-    if (e == hipSuccess) e = hipMalloc((void **)&d_cnt, 8);
-    if (e == hipSuccess) e = hipHostMalloc((void **)&h_cnt, 8, hipHostMallocDefault);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking);
-
-    size_t total = 0;
-    std::string err;
-    bool used[2] = {false, false};
-    for (uint64_t first = 0, i = 0; e == hipSuccess && err.empty() && first < slots; first += B, ++i) {
-        const int b = (int)(i & 1);
-        const size_t cnt_slots = (size_t)(slots - first < B ? slots - first : B);
-        if (used[b]) e = hipEventSynchronize(applied[b]);          // this pair of buffers is free again
-        if (e != hipSuccess) break;
-        if (hps_cache_dump(cache, (size_t)first, cnt_slots, d_keys[b], d_cnt + b, s2) != HPS_OK) {
-            err = std::string("dump: ") + hps_last_error();
-            break;
-        }
-        e = hipMemcpyAsync(h_cnt + b, d_cnt + b, 4, hipMemcpyDeviceToHost, s2);
-        if (e == hipSuccess) e = hipStreamSynchronize(s2);
-        if (e != hipSuccess) break;
-        const uint32_t m = h_cnt[b];
-        if (m == 0) continue;
-        e = hipMemcpyAsync(h_keys[b], d_keys[b], (size_t)m * 8, hipMemcpyDeviceToHost, s2);
-        if (e == hipSuccess) e = hipStreamSynchronize(s2);
-        if (e != hipSuccess) break;
-        fetch(user, h_keys[b], m, h_rows[b]);                       // steps 2-3: lower tiers, key-vector buffer
-        e = hipMemcpyAsync(d_rows[b], h_rows[b], (size_t)m * rowb, hipMemcpyHostToDevice, st);   // step 4
-        if (e != hipSuccess) break;
-        if (hps_cache_update(cache, d_keys[b], d_rows[b], m, st) != HPS_OK) {                    // step 5
-            err = std::string("update: ") + hps_last_error();
-            break;
-        }
-        e = hipEventRecord(applied[b], st);
-        used[b] = true;
-        total += m;
-    }
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (s2) (void)hipStreamSynchronize(s2);
-    for (int b = 0; b < 2; ++b) {
-        (void)hipFree(d_keys[b]); (void)hipFree(d_rows[b]);
-        (void)hipHostFree(h_keys[b]); (void)hipHostFree(h_rows[b]);
-        if (applied[b]) (void)hipEventDestroy(applied[b]);
-    }
-    (void)hipFree(d_cnt); (void)hipHostFree(h_cnt);
-    if (s2) (void)hipStreamDestroy(s2);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return lfail(e == hipErrorOutOfMemory ? HPS_ERR_OOM : HPS_ERR_DEVICE, std::string("hps_cache_refresh: ") + hipGetErrorString(e));
-    }
-    if (!err.empty()) return lfail(HPS_ERR_DEVICE, err);
-    if (n_refreshed) *n_refreshed = total;
-    return HPS_OK;
+    hps_refresh_t *R = nullptr;
+    if (hps_status_t s = hps_refresh_create(cache, batch_slots, &R)) return s;
+    const hps_status_t s = hps_refresh_run(R, fetch, user, n_refreshed, stream);
+    const std::string msg = g_lookup_err;
+    (void)hps_refresh_destroy(R);
+    if (s != HPS_OK) g_lookup_err = msg;
+    return s;
 }
 
 hps_status_t hps_lookup_drain(hps_lookup_t *L) {

@@ -97,10 +97,14 @@ def test_update_overlapping_queries_never_tears_rows(S, W, d, n_q, n_u):
         assert (mi_g == mi_o).all() and (out_g == out_o).all()
 
 
-def test_insert_overlapping_queries_keeps_rows_whole():
+@pytest.mark.parametrize("S,d,n_q,n_i", [(1 << 9, 128, 20000, 4096), (1 << 7, 320, 6000, 1024),
+                                         (1 << 7, 512, 6000, 1024), (1 << 6, 1024, 3000, 512)])
+def test_insert_overlapping_queries_keeps_rows_whole(S, d, n_q, n_i):
     """Queries racing with inserts (cache filling up and evicting): every row returned is the
-    complete row of its key (rows are a function of the key here), misses leave `out` untouched."""
-    S, W, d, n_q, n_i = 1 << 9, 8, 128, 20000, 4096
+    complete row of its key (rows are a function of the key here), misses leave `out` untouched.
+    Rows longer than 1 KiB (d > 256) are read in several wave loads: a key that an insert evicts
+    between them must come out as a miss whose `out` row still holds the sentinel in every word."""
+    W = 8
     rng = np.random.Generator(np.random.PCG64(99 + SEED_SHIFT))
     with DeviceCache(S * W, W, d, concurrent_writers=True) as gc:
         qs, ws = torch.cuda.Stream(), torch.cuda.Stream()
@@ -118,6 +122,7 @@ def test_insert_overlapping_queries_keeps_rows_whole():
             if qi % 2 == 0:
                 B.hps_cache_insert(gc.h, d_ins[qi // 2][0], d_ins[qi // 2][1], n_i, ws)
         torch.cuda.synchronize()
+        n_late = 0
         for qi in range(len(q_keys)):
             out = outs[qi].view(torch.int32).cpu().numpy().view(np.uint32)
             m = int(nm[qi].item())

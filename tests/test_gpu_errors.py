@@ -105,3 +105,25 @@ def test_create_reports_out_of_memory_and_recovers():
         gc.insert(keys, inputs.backing_rows(keys, 128))
         out, mi, _ = gc.query(keys)
         assert mi.size == 0 and (out == inputs.backing_rows(keys, 128).view(np.uint32)).all()
+
+
+def test_rows_too_long_to_validate_in_one_piece_cannot_overlap_writers():
+    """A query that overlaps writers stages a long row whole before it stores it; that is built for
+    rows of up to 4 KiB.  Longer rows: the cache starts in the no-overlap mode, switching the
+    validation on is refused, and the Alg. 1 object (whose background inserts overlap queries)
+    cannot be created on it.  Plain queries work."""
+    import numpy as np
+    from paper_2210_08804_amd import inputs
+    d = 1028
+    with DeviceCache(64, 8, d, concurrent_writers=False) as gc:
+        with pytest.raises(B.HpsError) as e:
+            B.hps_cache_set_concurrent_writers(gc.h, True)
+        assert e.value.status == B.HPS_ERR_INVALID_ARG and "dim" in str(e.value)
+        keys = np.arange(40, dtype=np.int64)
+        gc.insert(keys, inputs.backing_rows(keys, d))
+        out, mi, _ = gc.query(keys)
+        hit = np.ones(40, dtype=bool)
+        hit[mi] = False
+        assert hit.sum() >= 30 and (out[hit] == inputs.backing_rows(keys, d).view(np.uint32)[hit]).all()
+    with DeviceCache(64, 8, 1024, concurrent_writers=True):
+        pass                                                 # 4 KiB rows are fine

@@ -238,6 +238,17 @@ def test_refresh_cycle_from_the_host_map(batch_slots):
             oc.update(cached, inputs.backing_rows(cached, d, 1))
             assert_same_state(gc.export(), oc)
             assert B.hps_hostmap_stats(hm)[1] == 0                               # only stored keys were asked for
+            # the same through a session that is created once and run twice (its runs allocate nothing)
+            rs = B.hps_refresh_create(gc.h, batch_slots)
+            try:
+                for version in (2, 3):
+                    B.hps_hostmap_put(hm, keys, inputs.backing_rows(keys, d, version))
+                    assert B.hps_refresh_run(rs, B.hps_hostmap_fetch_fn(), user=hm) == len(cached)
+                    torch.cuda.synchronize()
+                    oc.update(cached, inputs.backing_rows(cached, d, version))
+                    assert_same_state(gc.export(), oc)
+            finally:
+                B.hps_refresh_destroy(rs)
         finally:
             B.hps_hostmap_destroy(hm)
 
