@@ -34,6 +34,7 @@ EXPORTS = (
     "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
     "hps_hostmap_create", "hps_hostmap_destroy", "hps_hostmap_put", "hps_hostmap_get", "hps_hostmap_fetch",
     "hps_hostmap_stats",
+    "hps_membench_gather", "hps_membench_copy",
 )
 
 # lower-tier fetch callback of hps_lookup.h: (user, keys*, n, rows*)
@@ -89,6 +90,8 @@ def load_library():
         "hps_hostmap_put": [vp, vp, vp, sz],
         "hps_hostmap_get": [vp, vp, sz, vp, C.POINTER(sz)],
         "hps_hostmap_stats": [vp, C.POINTER(sz), C.POINTER(sz)],
+        "hps_membench_gather": [vp, vp, sz, u32, vp, vp],
+        "hps_membench_copy": [vp, vp, sz, C.c_int, vp],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
         "hps_cache_insert": [vp, vp, vp, sz, vp],
@@ -253,6 +256,15 @@ def hps_backing_fetch(keys, n, dim, version=0, rows=None, n_dev=None, scatter_id
         _ptr(keys, torch.int64), n, _ptr(n_dev, torch.int32), dim, version,
         _ptr(rows, torch.float32), _ptr(scatter_idx, torch.int32),
         _ptr(scatter_out, torch.float32), _stream(stream)))
+
+
+def hps_membench_gather(rows, slot_of, n, dim, out, stream=None) -> None:
+    _check(load_library().hps_membench_gather(_ptr(rows, torch.float32), _ptr(slot_of, torch.int32), n, dim,
+                                              _ptr(out, torch.float32), _stream(stream)))
+
+
+def hps_membench_copy(src, dst, nbytes, nontemporal=True, stream=None) -> None:
+    _check(load_library().hps_membench_copy(_ptr(src), _ptr(dst), nbytes, 1 if nontemporal else 0, _stream(stream)))
 
 
 def hps_last_error() -> str:

@@ -28,6 +28,7 @@
 #include <unordered_map>
 
 #include "hps_cache.h"
+#include "hps_membench.h"
 #include "hps_mix.h"
 
 namespace {
@@ -148,10 +149,13 @@ struct RowGeom {
 // (or beyond the row, when d/4 is not a power of two) repeat entry 0 / chunk 0, i.e. they store
 // the same bytes to the same place as a live lane, and the loads issued past the last group
 // re-read entry 0 and are dropped.
-template <int U, typename SrcIdx, typename DstIdx>
+//
+// kTwoBuffers = false is the same loop with one buffer (load U, store U): batches of 2^18 keys and
+// more, whose work-groups run several to a CU, measured 5 % faster with one buffer of 8.
+template <int U, bool kTwoBuffers = true, typename SrcIdx, typename DstIdx>
 __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restrict__ src,
                                           float *__restrict__ dst, const SrcIdx *srcRow,
-                                          const DstIdx *dstRow, uint32_t cnt, bool nontemporal = true) {
+                                          const DstIdx *dstRow, uint32_t cnt) {
     const uint32_t lane = (uint32_t)lane_id();
     const uint32_t rpi = (uint32_t)kWave >> g.lprShift;      // rows per wave load
     const uint32_t sub = lane >> g.lprShift;                 // which of those rows this lane serves
@@ -175,19 +179,26 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
         auto store = [&](const f32x4 (&buf)[U], const uint64_t (&dp)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                f32x4 *q = reinterpret_cast<f32x4 *>(dst + dp[u] * g.d + off);
-                if (nontemporal) __builtin_nontemporal_store(buf[u], q);
-                else *q = buf[u];
+                // non-temporal: rows of `out` are written once and not read again here (24.9 us per
+                // 106,496-key batch with plain stores against 22.9 us)
+                __builtin_nontemporal_store(buf[u], reinterpret_cast<f32x4 *>(dst + dp[u] * g.d + off));
             }
         };
-        load(0, bufA, dpA);
-        for (uint32_t e0 = 0;; e0 += 2 * step) {
-            load(e0 + step, bufB, dpB);
-            store(bufA, dpA);
-            if (e0 + step >= cnt) break;
-            load(e0 + 2 * step, bufA, dpA);
-            store(bufB, dpB);
-            if (e0 + 2 * step >= cnt) break;
+        if (kTwoBuffers) {
+            load(0, bufA, dpA);
+            for (uint32_t e0 = 0;; e0 += 2 * step) {
+                load(e0 + step, bufB, dpB);
+                store(bufA, dpA);
+                if (e0 + step >= cnt) break;
+                load(e0 + 2 * step, bufA, dpA);
+                store(bufB, dpB);
+                if (e0 + 2 * step >= cnt) break;
+            }
+        } else {
+            for (uint32_t e0 = 0; e0 < cnt; e0 += step) {
+                load(e0, bufA, dpA);
+                store(bufA, dpA);
+            }
         }
     }
 }
@@ -406,7 +417,7 @@ __device__ __forceinline__ void finish_call(const QueryArgs &a, uint32_t n_miss,
 // (odd word), copies rows with copy_rows_checked and repeats for the keys whose set changed under
 // it.  A miss needs no check (an 8-byte key is read whole, and a key that stays cached is never
 // absent from its slot), so only hits are validated.
-template <int W, int KPW, int U, int WPB, bool kCoherent>
+template <int W, int KPW, int U, int WPB, bool kCoherent, bool kTwoBuffers = true>
 __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArgs a) {
     __shared__ uint64_t s_src[WPB][KPW];
     __shared__ uint32_t s_dst[WPB][KPW];
@@ -520,7 +531,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 }
                 wave_lds_fence();
                 if (lane == 0) __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (nh) copy_rows<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
+                if (nh) copy_rows<U, kTwoBuffers>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
             }
         } else {
             if (kCoherent) {
@@ -1068,6 +1079,50 @@ __global__ void backing_kernel(const int64_t *__restrict__ keys, uint32_t n,
     }
 }
 
+// ------------------------------------------------------------------ measurement kernels (hps_membench.h)
+
+// The row movement of query_kernel's plain variant alone: same tile shape, same copy loop, but the
+// source slot of every position is given, so nothing is hashed, probed or compacted.
+template <int U, int WPB>
+__global__ void __launch_bounds__(WPB * kWave) membench_gather_kernel(const float *__restrict__ rows,
+                                                                      const uint32_t *__restrict__ slot_of, uint32_t n,
+                                                                      uint32_t kpw, const RowGeom g, float *__restrict__ out) {
+    __shared__ uint32_t s_src[WPB][kWave];
+    __shared__ uint32_t s_dst[WPB][kWave];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    const uint32_t pos = (blockIdx.x * WPB + wave) * kpw + lane;
+    const bool inb = lane < (int)kpw && pos < n;
+    const uint32_t sl = inb ? slot_of[pos] : 0xFFFFFFFFu;
+    const bool hit = sl != 0xFFFFFFFFu;
+    const uint64_t hitmask = __ballot(hit);
+    const uint32_t nh = (uint32_t)__popcll(hitmask);
+    if (hit) {
+        const int r = rank_in(hitmask);
+        s_src[wave][r] = sl;
+        s_dst[wave][r] = pos;
+    }
+    wave_lds_fence();
+    if (nh) copy_rows<U>(g, rows, out, &s_src[wave][0], &s_dst[wave][0], nh);
+}
+
+template <int U, bool kNT>
+__global__ void __launch_bounds__(kBlock) membench_copy_kernel(const f32x4 *__restrict__ src, f32x4 *__restrict__ dst, uint64_t n16) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        f32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = kNT ? __builtin_nontemporal_load(src + i + u * stride) : src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (kNT) __builtin_nontemporal_store(x[u], dst + i + u * stride);
+            else dst[i + u * stride] = x[u];
+        }
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------ host side
 
 RowGeom make_geom(uint32_t d) {
@@ -1167,19 +1222,20 @@ uint64_t *counter_word(hps_cache *c, void *stream) {
 struct QueryShape { int kpw, u, wpb; };
 
 QueryShape query_shape(uint64_t n) {
-    if (n < (1u << 16)) return QueryShape{64, 2, 4};
-    if (n < (1u << 18)) return QueryShape{64, 2, 8};
-    return QueryShape{64, 4, 4};
+    if (n < (1u << 16)) return QueryShape{64, 2, 4};      // two buffers of 2 wave loads
+    if (n < (1u << 18)) return QueryShape{64, 2, 8};      // two buffers of 2 wave loads
+    return QueryShape{64, 8, 4};                          // one buffer of 8 wave loads
 }
 
 template <int W, int KPW, int U, int WPB>
 void launch_query_shape(const QueryArgs &a, bool coherent, bool dedup, hipStream_t st) {
+    constexpr bool kTwo = U < 8;
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
     if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true>), dim3(grid), block, 0, st, a);
     else if (dedup && KPW == kWave)
-        hipLaunchKernelGGL((query_dedup_kernel<W, 2 * U, WPB>), dim3(grid), block, 0, st, a);
-    else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false>), dim3(grid), block, 0, st, a);
+        hipLaunchKernelGGL((query_dedup_kernel<W, (kTwo ? 2 * U : U), WPB>), dim3(grid), block, 0, st, a);
+    else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, kTwo>), dim3(grid), block, 0, st, a);
 }
 
 template <int W>
@@ -1188,7 +1244,7 @@ hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, boo
     switch (id) {
         case 640204: launch_query_shape<W, 64, 2, 4>(a, coherent, dedup, st); break;
         case 640208: launch_query_shape<W, 64, 2, 8>(a, coherent, dedup, st); break;
-        case 640404: launch_query_shape<W, 64, 4, 4>(a, coherent, dedup, st); break;
+        case 640804: launch_query_shape<W, 64, 8, 4>(a, coherent, dedup, st); break;
         default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
     }
     HIP_TRY(hipGetLastError());
@@ -1549,6 +1605,52 @@ hps_status_t hps_cache_dump(hps_cache_t *c, size_t first_slot, size_t n_slots, i
     const uint32_t grid = n_tiles < (1u << 20) ? n_tiles : (1u << 20);
     hipLaunchKernelGGL((dump_kernel<kDumpKpt>), dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), c->K,
                        (uint64_t)first_slot, (uint64_t)n_slots, keys_out, n_out, counter_word(c, stream), n_tiles);
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t hps_membench_gather(const float *rows, const uint32_t *slot_of, size_t n, uint32_t dim, float *out,
+                                 void *stream) {
+    if (dim == 0 || dim % 4 != 0) return fail(HPS_ERR_INVALID_ARG, "dim must be a non-zero multiple of 4");
+    if (n == 0) return HPS_OK;
+    if (n >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n must be < 2^32");
+    if (!rows || !slot_of || !out) return fail(HPS_ERR_INVALID_ARG, "rows, slot_of and out must not be NULL");
+    if (!aligned(rows, 16) || !aligned(out, 16) || !aligned(slot_of, 4)) return fail(HPS_ERR_INVALID_ARG, "misaligned buffer");
+    int dev = 0, cus = 256;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus <= 0) cus = 256;
+    // the query kernel's shape for this batch size: 8 waves x up to 64 positions, trimmed to whole rounds over the CUs
+    constexpr int kWpb = 8;
+    const uint64_t full = (uint64_t)kWpb * kWave * (uint64_t)cus;
+    const uint64_t rounds = (n + full - 1) / full;
+    uint64_t kpw = (n + kWpb * (uint64_t)cus * rounds - 1) / (kWpb * (uint64_t)cus * rounds);
+    if (kpw < 16) kpw = 16;
+    if (kpw > (uint64_t)kWave) kpw = kWave;
+    const uint64_t tile = kpw * kWpb;
+    const uint64_t blocks = (n + tile - 1) / tile;
+    if (blocks >= (1ull << 31)) return fail(HPS_ERR_INVALID_ARG, "n too large");
+    hipLaunchKernelGGL((membench_gather_kernel<2, kWpb>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0,
+                       static_cast<hipStream_t>(stream), rows, slot_of, (uint32_t)n, (uint32_t)kpw, make_geom(dim), out);
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t hps_membench_copy(const void *src, void *dst, size_t bytes, int nontemporal, void *stream) {
+    if (bytes == 0) return HPS_OK;
+    if (!src || !dst || bytes % 16 != 0 || !aligned(src, 16) || !aligned(dst, 16))
+        return fail(HPS_ERR_INVALID_ARG, "src and dst must be 16-byte aligned and bytes a multiple of 16");
+    const uint64_t n16 = bytes / 16;
+    uint64_t blocks = (n16 + (uint64_t)kBlock * 8 - 1) / ((uint64_t)kBlock * 8);
+    if (blocks > 16384) blocks = 16384;
+    if (blocks == 0) blocks = 1;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (nontemporal)
+        hipLaunchKernelGGL((membench_copy_kernel<8, true>), dim3((uint32_t)blocks), dim3(kBlock), 0, st,
+                           static_cast<const f32x4 *>(src), static_cast<f32x4 *>(dst), n16);
+    else
+        hipLaunchKernelGGL((membench_copy_kernel<8, false>), dim3((uint32_t)blocks), dim3(kBlock), 0, st,
+                           static_cast<const f32x4 *>(src), static_cast<f32x4 *>(dst), n16);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
