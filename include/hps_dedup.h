@@ -52,6 +52,19 @@ hps_status_t hps_dedup_destroy(hps_dedup_t *s);
 hps_status_t hps_dedup(hps_dedup_t *s, const int64_t *keys, size_t n, int64_t *unique_keys,
                        uint32_t *inverse, uint32_t *n_unique, void *stream);
 
+/* hps_dedup for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments and results as hps_dedup, but
+ * no session: the hash table lives in a static device array of the library (3 MiB per GPU, held
+ * until the process ends), so the call allocates and frees nothing (no hipMalloc, no hipFree, no
+ * allocating library routine); it only launches three kernels on `stream`.  At most
+ * HPS_DEDUP_NOALLOC_MAX keys per call: a larger n returns HPS_ERR_INVALID_ARG and launches
+ * nothing.  Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (on
+ * different streams, or from different threads without ordering) race and must be ordered by the
+ * caller; calls on one stream are ordered.  The current device is the one the call works on. */
+#define HPS_DEDUP_NOALLOC_MAX 131072u
+hps_status_t hps_dedup_noalloc(const int64_t *keys, size_t n, int64_t *unique_keys, uint32_t *inverse,
+                               uint32_t *n_unique, void *stream);
+
 /* out[i] = rows[inverse[i]] for i < n: the step after the lookup of Q* (Sec. 2.2).
  *   rows    device, [u][dim] 32-bit words, read only; every inverse[i] must be < u (not checked)
  *   inverse device, uint32 [n]

@@ -32,6 +32,7 @@ EXPORTS = (
     "hps_lookup_create", "hps_lookup", "hps_lookup_drain", "hps_lookup_destroy", "hps_lookup_last_error",
     "hps_cache_refresh", "hps_refresh_create", "hps_refresh_run", "hps_refresh_destroy",
     "hps_dedup_create", "hps_dedup_destroy", "hps_dedup", "hps_expand_rows", "hps_dedup_last_error",
+    "hps_dedup_noalloc",
     "hps_hostmap_create", "hps_hostmap_destroy", "hps_hostmap_put", "hps_hostmap_get", "hps_hostmap_fetch",
     "hps_hostmap_stats",
     "hps_membench_gather", "hps_membench_copy",
@@ -84,6 +85,7 @@ def load_library():
         "hps_dedup_create": [sz, C.POINTER(vp)],
         "hps_dedup_destroy": [vp],
         "hps_dedup": [vp, vp, sz, vp, vp, vp, vp],
+        "hps_dedup_noalloc": [vp, sz, vp, vp, vp, vp],
         "hps_expand_rows": [vp, vp, sz, u32, vp, vp],
         "hps_hostmap_create": [u32, u32, sz, C.POINTER(vp)],
         "hps_hostmap_destroy": [vp],
@@ -357,6 +359,16 @@ def hps_dedup_destroy(session) -> None:
 def hps_dedup(session, keys, n, unique_keys, inverse, n_unique, stream=None) -> None:
     _check_dedup(load_library().hps_dedup(
         session, _ptr(keys, torch.int64), n, _ptr(unique_keys, torch.int64), _ptr(inverse, torch.int32),
+        _ptr(n_unique, torch.int32), _stream(stream)))
+
+
+HPS_DEDUP_NOALLOC_MAX = 131072
+
+
+def hps_dedup_noalloc(keys, n, unique_keys, inverse, n_unique, stream=None) -> None:
+    """hps_dedup without a session: the table is a static device array of the library."""
+    _check_dedup(load_library().hps_dedup_noalloc(
+        _ptr(keys, torch.int64), n, _ptr(unique_keys, torch.int64), _ptr(inverse, torch.int32),
         _ptr(n_unique, torch.int32), _stream(stream)))
 
 

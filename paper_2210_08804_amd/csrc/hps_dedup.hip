@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -32,6 +33,22 @@ constexpr uint64_t kMagic = 0x4850534445445550ull;
 constexpr uint32_t kNone  = 0xFFFFFFFFu;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Scratch of hps_dedup_noalloc, the entry point for callers that cannot allocate: one hash table
+// for batches of up to kNaMaxKeys keys (2 slots per key, 8-byte key word + 4-byte number per
+// slot, one extra slot for the key that equals the free marker) and its counter words, in a
+// static device array (3 MiB that every GPU the library runs on holds until the process ends).
+constexpr uint32_t kNaMaxKeys  = HPS_DEDUP_NOALLOC_MAX;
+constexpr uint32_t kNaSlots    = 2 * kNaMaxKeys;                        // a power of two
+constexpr size_t   kNaKeyBytes = (((size_t)kNaSlots + 1) * 8 + 255) / 256 * 256;
+constexpr size_t   kNaUidBytes = (((size_t)kNaSlots + 1) * 4 + 255) / 256 * 256;
+constexpr size_t   kNaBytes    = kNaKeyBytes + kNaUidBytes + 256;       // + two counter words
+static_assert((kNaSlots & (kNaSlots - 1)) == 0, "slot count must be a power of two");
+static __device__ __align__(256) unsigned char scratch[kNaBytes];
+
+constexpr int kNaMaxDevices = 64;
+std::mutex g_na_mu;
+unsigned char *g_na_ptr[kNaMaxDevices];          // device address of `scratch` on each device, once known
 
 thread_local std::string g_err;
 
@@ -342,6 +359,61 @@ hps_status_t hps_dedup(hps_dedup_t *s, const int64_t *keys, size_t n, int64_t *u
     s->dirty[t] = slots + 1;          // this call's slots, the extra one included
     s->dirty[o] = 0;
     s->cur = o;
+    return HPS_OK;
+}
+
+hps_status_t hps_dedup_noalloc(const int64_t *keys, size_t n, int64_t *unique_keys, uint32_t *inverse,
+                               uint32_t *n_unique, void *stream) {
+    if (!n_unique || !aligned(n_unique, 4)) return fail(HPS_ERR_INVALID_ARG, "n_unique must be a 4-byte aligned device pointer");
+    if (n > kNaMaxKeys)
+        return fail(HPS_ERR_INVALID_ARG, "hps_dedup_noalloc takes at most " + std::to_string(kNaMaxKeys) +
+                                             " keys per call (its table is a fixed static array); use a session of hps_dedup for more");
+    hipStream_t q = static_cast<hipStream_t>(stream);
+    if (n == 0) {
+        hipLaunchKernelGGL(set_u32_kernel, dim3(1), dim3(1), 0, q, n_unique, 0u);
+        HIP_TRY(hipGetLastError());
+        return HPS_OK;
+    }
+    if (!keys || !unique_keys || !inverse) return fail(HPS_ERR_INVALID_ARG, "keys, unique_keys and inverse must not be NULL when n > 0");
+    if (!aligned(keys, 8) || !aligned(unique_keys, 8) || !aligned(inverse, 4))
+        return fail(HPS_ERR_INVALID_ARG, "keys and unique_keys must be 8-byte, inverse 4-byte aligned");
+    // The array's name is only a host-side stand-in: its device address is asked for once per
+    // device (each GPU holds its own copy at its own address) and used from then on.
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kNaMaxDevices) return fail(HPS_ERR_INVALID_ARG, "device number beyond what hps_dedup_noalloc keeps track of");
+    unsigned char *base = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_na_mu);
+        if (!g_na_ptr[dev]) {
+            void *p = nullptr;
+            HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) return fail(HPS_ERR_DEVICE, "hipGetSymbolAddress returned no address for the scratch array");
+            g_na_ptr[dev] = static_cast<unsigned char *>(p);
+        }
+        base = g_na_ptr[dev];
+    }
+    int64_t  *tkey    = reinterpret_cast<int64_t *>(base);
+    uint32_t *tuid    = reinterpret_cast<uint32_t *>(base + kNaKeyBytes);
+    uint32_t *counter = reinterpret_cast<uint32_t *>(base + kNaKeyBytes + kNaUidBytes);
+    int n_cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n_cus <= 0) n_cus = 256;
+    const uint64_t slots = pow2_at_least(2 * (uint64_t)n);            // <= kNaSlots because n <= kNaMaxKeys
+    const uint32_t mask = (uint32_t)(slots - 1);
+    const uint32_t cap = (uint32_t)n_cus * 8u;
+    const uint64_t tiles = (n + kTile - 1) / kTile;
+    // The array keeps what the last call left in it: the slots this call may touch and its counter
+    // are cleared first (by a kernel, so that the call can be captured into a graph), then the
+    // same two launches as hps_dedup.
+    const uint64_t cb = (slots + 1 + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(dedup_clear_kernel, dim3((uint32_t)(cb < cap ? cb : cap)), dim3(kBlock), 0, q, tkey, slots + 1, counter);
+    hipLaunchKernelGGL(dedup_insert_kernel, dim3((uint32_t)(tiles < cap ? tiles : cap)), dim3(kTile), 0, q,
+                       keys, (uint32_t)n, tkey, tuid, mask, counter, unique_keys);
+    const uint64_t ib = (n + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(dedup_inverse_kernel, dim3((uint32_t)(ib < 4 * cap ? ib : 4 * cap)), dim3(kBlock), 0, q,
+                       keys, (uint32_t)n, tkey, tuid, mask, counter, inverse, n_unique, tkey, (uint64_t)0, counter + 1);
+    HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
 
