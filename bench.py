@@ -11,6 +11,7 @@ bytes per launch / measured time per launch / 8 TB/s) and the CPU oracle timed o
 cores on a bounded sample of the same batches.
 """
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -59,6 +60,12 @@ def parse():
                    help="lookup: concurrent workers (threads), each with its own lookup object and stream, on one cache")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-batches", type=int, default=100)
+    p.add_argument("--batched", type=int, default=4,
+                   help="also time the same batches k per launch (0 or 1: skip)")
+    p.add_argument("--no-checked", dest="also_checked", action="store_false",
+                   help="skip the extra timing of the checked (library default) query mode")
+    p.add_argument("--no-ceiling", dest="ceiling", action="store_false",
+                   help="skip the ceiling measurement (row gather with given slots, streaming copy)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one plain 1 GiB device copy (reference for the rocprofv3 byte counters)")
     return p.parse_args()
@@ -67,6 +74,51 @@ def parse():
 # Paper, Table 3 (A100-80GB, fp32 rows of 128): cache capacity GB -> (update ms, dump ms)
 PAPER_REFRESH = {1: (5.152, 0.064), 5: (25.177, 0.184), 10: (50.262, 0.335), 20: (100.530, 0.641),
                  40: (200.345, 1.19)}
+
+
+def roofline_obj(kernel, alg_bytes, us, traffic=None, **extra):
+    """HBM roofline of one kernel: algorithmic bytes per launch / measured time per launch / 8 TB/s."""
+    gbs = alg_bytes / (us * 1e-6) / 1e9
+    r = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": kernel,
+         "algorithmic_bytes_per_launch": int(round(alg_bytes)), "us_per_launch": round(us, 3)}
+    r.update(extra)
+    return r
+
+
+def query_alg_bytes(np, keys, miss_idx, d):
+    """Algorithmic bytes of one query launch over the positions `keys` with the miss positions
+    `miss_idx` (indices into keys): 8n + 64 D + 4d D_h + 4d n_h + 12 n_m + 4."""
+    n, m = len(keys), len(miss_idx)
+    D = np.unique(keys).size
+    D_m = np.unique(keys[miss_idx]).size if m else 0
+    return 8 * n + 64 * D + 4 * d * (D - D_m) + 4 * d * (n - m) + 12 * m + 4
+
+
+def event_us(torch, fn, reps, warm=2):
+    """Microseconds per call of fn() on the current stream (HIP events around `reps` calls)."""
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def oracle_hot_cache(np, slots, W, d, chunk=1 << 18):
+    """The CPU oracle with the hot-cache prefill (ids slots-1 .. 0 in descending chunks)."""
+    from oracle import OracleCache
+    oc = OracleCache(slots, W, d)
+    rng = np.random.Generator(np.random.PCG64(0))
+    filler = rng.integers(0, 1 << 32, size=(chunk, d), dtype=np.uint32)     # row content is irrelevant to timing
+    for hi in range(slots, 0, -chunk):
+        lo = max(0, hi - chunk)
+        oc.insert(np.arange(hi - 1, lo - 1, -1, dtype=np.int64), filler[: hi - lo])
+    return oc, filler
 
 
 def refresh(a, np, torch, B):
@@ -138,6 +190,23 @@ def refresh(a, np, torch, B):
                      "kernel": "update_kernel<8>", "algorithmic_bytes_per_launch": alg,
                      "us_per_launch": round(upd_ms * 1e3, 1)},
     }
+    if not a.no_cpu_baseline:
+        # the oracle's Dump + Update on a bounded sample: a cache of 2^21 slots of the same row width
+        from oracle import OracleCache
+        cs = 1 << 21
+        oc = OracleCache(cs, W, d)
+        ids = np.arange(2 * cs, dtype=np.int64)
+        filler = np.random.Generator(np.random.PCG64(0)).integers(0, 1 << 32, size=(1 << 18, d), dtype=np.uint32)
+        for lo in range(0, 2 * cs, 1 << 18):
+            oc.insert(ids[lo:lo + (1 << 18)], filler)
+        t0 = time.perf_counter()
+        dumped = oc.dump()
+        for lo in range(0, len(dumped), 1 << 18):
+            oc.update(dumped[lo:lo + (1 << 18)], filler[: len(dumped[lo:lo + (1 << 18)])])
+        t1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(len(dumped) * 4 * d / (t1 - t0) / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"dump + update of all {len(dumped)} cached rows of a {cs}-slot cache of the same row width"}
+        oc.close()
     torch.cuda.synchronize()
     B.hps_cache_destroy(h)
     print(json.dumps(res))
@@ -173,24 +242,54 @@ def stream_fill(a, np, torch, B, inputs):
     mk = torch.empty(n, dtype=torch.int64, device="cuda")
     nm = torch.zeros(steps, dtype=torch.int32, device="cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evq = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    mis = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(4)]      # the last steps' miss lists are kept
     torch.cuda.synchronize()
     ev[0].record()
     for s in range(steps):
+        mi = mis[s % 4]
         B.hps_cache_query(h, keys[s], n, out, mi, mk, nm[s:s + 1])
+        evq[s].record()
         B.hps_backing_fetch(mk, n, d, version=0, rows=rows, n_dev=nm[s:s + 1], scatter_idx=mi, scatter_out=out)
         B.hps_cache_insert_dn(h, mk, rows, n, nm[s:s + 1])
         ev[s + 1].record()
     torch.cuda.synchronize()
     ms = np.array([ev[s].elapsed_time(ev[s + 1]) for s in range(steps)])
+    q_us = np.array([ev[s].elapsed_time(evq[s]) for s in range(steps)]) * 1e3
     hit = 1.0 - nm.cpu().numpy() / n
     tail = slice(steps // 2, steps)
+    # algorithmic bytes of the query launches of the last four steps (their miss lists are still there)
+    algs = []
+    for s in range(max(0, steps - 4), steps):
+        m = int(nm[s].item())
+        algs.append(query_alg_bytes(np, keys[s].cpu().numpy(), mis[s % 4][:m].cpu().numpy().view(np.uint32), d))
     res = {"metric": "streaming lookup Mkeys/s (query + miss fill + insert per step)", "value": round(n / (ms[tail].mean() * 1e-3) / 1e6, 1),
            "unit": "Mkeys/s", "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": round(float(ms[tail].mean()), 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
            "config": {"workload": f"streaming query + miss fill: {S} sets x {W} ways, dim {d}, {n} Zipf(1.1) keys over 1e8 per step, cold start",
                       "replacement_policy": a.policy,
                       "hit_rate_per_step": [round(float(x), 4) for x in hit[: 10]] + ["..."] + [round(float(x), 4) for x in hit[-5:]],
-                      "ms_per_step_first10": [round(float(x), 3) for x in ms[:10]]}}
+                      "ms_per_step_first10": [round(float(x), 3) for x in ms[:10]],
+                      "query_us_per_step_last4": [round(float(x), 1) for x in q_us[-4:]]},
+           "roofline": roofline_obj("query_kernel<ways=8, checked=False> (the longest of the step's three kernels)",
+                                    float(np.mean(algs)), float(np.mean(q_us[-4:])))}
+    if not a.no_cpu_baseline:
+        # the oracle running the same steps (query, rows of the missing keys from the generator, insert): first 12 steps
+        from oracle import OracleCache
+        oc = OracleCache(S * W, W, d, policy=0 if a.policy == "counter" else 1)
+        nb = min(12, steps)
+        out_cpu = np.empty((n, d), dtype=np.uint32)
+        hk = [keys[s].cpu().numpy() for s in range(nb)]
+        t0 = time.perf_counter()
+        for s in range(nb):
+            _, omi, omk = oc.query(hk[s], out_cpu)
+            r = inputs.backing_rows(omk, d, 0)
+            out_cpu[omi] = r.view(np.uint32)
+            oc.insert(omk, r)
+        t1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(nb * n / (t1 - t0) / 1e6, 2), "unit": "Mkeys/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {nb} steps of the same key stream (cold start, so more misses per step than the stable stage)"}
+        oc.close()
     torch.cuda.synchronize()
     B.hps_cache_destroy(h)
     print(json.dumps(res))
@@ -248,7 +347,18 @@ def dedup_lookup(a, np, torch, B, inputs):
            "config": {"workload": f"dedup in front of the hot-cache query: {S} sets x {W} ways, dim {d}, {n} Zipf({a.alpha}) keys over {a.key_space}",
                       "distinct_fraction": round(float(n_u.mean()) / n, 4),
                       "us": {"direct_query": round(t_direct, 2), "dedup": round(t_dedup, 2), "query_distinct": round(t_q, 2),
-                             "expand": round(t_x, 2), "dedup+query+expand": round(t_path, 2)}}}
+                             "expand": round(t_x, 2), "dedup+query+expand": round(t_path, 2)}},
+           # expand is the stage that moves the bytes: n rows written, the distinct rows read, 4 bytes of map per position
+           "roofline": roofline_obj("expand_rows_kernel", float(n * 4 * d + n_u.mean() * 4 * d + 4 * n), t_x,
+                                    note="the dedup kernels themselves move 20 bytes per key and are bound by dependent atomics, not by bytes")}
+    if not a.no_cpu_baseline:
+        import oracle
+        hk = keys[warm].cpu().numpy()
+        t0 = time.perf_counter()
+        ou, oinv = oracle.dedup(hk)
+        t1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(n / (t1 - t0) / 1e6, 3), "unit": "Mkeys/s", "cores": 1, "kind": "oracle",
+                               "sample": "dedup of one batch by the oracle's definition (every key compared with the distinct keys so far)"}
     torch.cuda.synchronize()
     B.hps_dedup_destroy(dd)
     B.hps_cache_destroy(h)
@@ -289,9 +399,26 @@ def write_batches(a, np, torch, B, inputs):
            "config": {"workload": f"insert of {n} new keys, then update of the same keys: {S} sets x {W} ways, dim {d}",
                       "insert_us": round(ins_us, 1), "update_us": round(upd_us, 1),
                       "insert_rows_GBps": round(n * 2 * row_b / ins_us / 1e3, 1), "update_rows_GBps": round(n * 2 * row_b / upd_us / 1e3, 1)},
-           "roofline": {"bound": "hbm", "achieved": round(alg_ins / ins_us / 1e3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(alg_ins / ins_us / 1e3 / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "insert_kernel<8,16>",
-                        "algorithmic_bytes_per_launch": alg_ins, "us_per_launch": round(ins_us, 1)}}
+           "roofline": roofline_obj("insert_kernel<8,16>", alg_ins, ins_us),
+           "roofline_update": roofline_obj("update_kernel<8,64>", n * (8 + 64 + 2 * row_b + 8), upd_us)}
+    if not a.no_cpu_baseline:
+        from oracle import OracleCache
+        oc = OracleCache(S * W, W, d)
+        hrows = rows.cpu().numpy().view(np.uint32)
+        nb = min(steps, 8)
+        t_i = t_u = 0.0
+        for c in range(nb):
+            k = np.arange(c * n, (c + 1) * n, dtype=np.int64)
+            t0 = time.perf_counter()
+            oc.insert(k, hrows)
+            t1 = time.perf_counter()
+            oc.update(k, hrows)
+            t2 = time.perf_counter()
+            t_i += t1 - t0
+            t_u += t2 - t1
+        res["cpu_baseline"] = {"value": round(nb * n / (t_i + t_u) / 1e6, 2), "unit": "Mrows/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {nb} batches of the same keys: insert {round(nb * n / t_i / 1e6, 2)} Mrows/s, update {round(nb * n / t_u / 1e6, 2)} Mrows/s"}
+        oc.close()
     torch.cuda.synchronize()
     B.hps_cache_destroy(h)
     print(json.dumps(res))
@@ -407,6 +534,37 @@ def lookup_alg1(a, np, torch, B, inputs):
                       "hit_rate_stable": round(float(np.mean(rate[steps // 2:])), 4)}}
     B.hps_lookup_destroy(lk)
     torch.cuda.synchronize()
+    # The call's time is host work (one stream synchronisation, the call sequence, the lower tier);
+    # the one kernel that moves rows is the checked query, timed here alone on the last batches
+    mi = torch.empty(n, dtype=torch.int32, device="cuda")
+    mk = torch.empty(n, dtype=torch.int64, device="cuda")
+    nm = torch.zeros(1, dtype=torch.int32, device="cuda")
+    cnt = [0]
+
+    def one():
+        B.hps_cache_query(h, keys[steps - 1 - cnt[0] % 8], n, out, mi, mk, nm)
+        cnt[0] += 1
+    q_us = event_us(torch, one, 200, warm=8)
+    B.hps_cache_query(h, keys[steps - 1], n, out, mi, mk, nm)
+    torch.cuda.synchronize()
+    m0 = int(nm.item())
+    alg = query_alg_bytes(np, keys[steps - 1].cpu().numpy(), mi[:m0].cpu().numpy().view(np.uint32), d)
+    res["roofline"] = roofline_obj("query_kernel<ways=8, checked=True> (the call's row-moving kernel, timed alone)", alg, q_us,
+                                   note="a lookup call is bound by host work and the lower tier, not by this kernel")
+    if not a.no_cpu_baseline:
+        # the oracle's Alg. 1 on the first 40 calls, rows of the lower tier from the generator
+        from oracle import OracleCache
+        oc = OracleCache(S * W, W, d, policy=0 if a.policy == "counter" else 1)
+        nb = min(40, steps)
+        hk = [keys[s].cpu().numpy() for s in range(nb)]
+        lower = [inputs.backing_rows(k, d, 0) for k in hk]
+        t0 = time.perf_counter()
+        for s in range(nb):
+            oc.lookup(hk[s], lower[s], a.threshold, np.zeros(d, np.float32))
+        t1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(nb * n / (t1 - t0) / 1e6, 2), "unit": "Mkeys/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {nb} calls of the same key stream (cold start), lower-tier rows prepared beforehand"}
+        oc.close()
     B.hps_cache_destroy(h)
     B.hps_hostmap_destroy(hm)
     print(json.dumps(res))
@@ -437,11 +595,13 @@ def refresh_from_host(a, np, torch, B, inputs):
     fetch = B.hps_hostmap_fetch_fn()
     steps = max(1, min(a.steps, 5))
     times, n = [], 0
+    rs = B.hps_refresh_create(h, 1 << 18)                  # buffers, stream and events allocated once
     for _ in range(steps):
         t0 = _time.perf_counter()
-        n = B.hps_cache_refresh(h, 1 << 18, fetch, user=hm)
+        n = B.hps_refresh_run(rs, fetch, user=hm)
         torch.cuda.synchronize()
         times.append(_time.perf_counter() - t0)
+    B.hps_refresh_destroy(rs)
     ms = float(np.median(times)) * 1e3
     gb = n * 4 * d / 1e9
     res = {"metric": "cache refresh from a host-memory lower tier, GB/s of cached rows", "value": round(gb / (ms * 1e-3), 2), "unit": "GB/s",
@@ -449,6 +609,34 @@ def refresh_from_host(a, np, torch, B, inputs):
            "vs_baseline": None, "dtype": "int64", "data": "synthetic",
            "config": {"workload": f"hps_cache_refresh: {n} cached rows of dim {d} ({gb:.2f} GB), batches of 262144 slots, lower tier = host map of {n_keys} keys",
                       "Mkeys_per_s": round(n / (ms * 1e-3) / 1e6, 1)}}
+    # the cycle is bound by the host map; its row-moving kernel is the Update of one batch of 2^18 slots, timed alone
+    m = 1 << 18
+    dk = torch.empty(m, dtype=torch.int64, device="cuda")
+    cntw = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.hps_cache_dump(h, 0, m, dk, cntw)
+    torch.cuda.synchronize()
+    mm = int(cntw.item())
+    drows = torch.empty(m, d, dtype=torch.float32, device="cuda")
+    B.hps_backing_fetch(dk, mm, d, version=1, rows=drows)
+    u_us = event_us(torch, lambda: B.hps_cache_update(h, dk, drows, mm), 20, warm=2)
+    res["roofline"] = roofline_obj("update_kernel<8,64> (one batch of the cycle, timed alone)",
+                                   mm * (8 + 2 * 4 * d) + (m // W) * (8 * W + 8), u_us,
+                                   note="the refresh cycle as a whole is bound by the host-memory lower tier")
+    if not a.no_cpu_baseline:
+        from oracle import OracleCache
+        oc = OracleCache(S * W, W, d)
+        ids = np.arange(n_keys, dtype=np.int64)
+        filler = np.random.Generator(np.random.PCG64(0)).integers(0, 1 << 32, size=(1 << 18, d), dtype=np.uint32)
+        for lo in range(0, n_keys, 1 << 18):
+            oc.insert(ids[lo:lo + (1 << 18)], filler)
+        t0 = _time.perf_counter()
+        dumped = oc.dump()
+        for lo in range(0, len(dumped), 1 << 18):
+            oc.update(dumped[lo:lo + (1 << 18)], filler[: len(dumped[lo:lo + (1 << 18)])])
+        t1 = _time.perf_counter()
+        res["cpu_baseline"] = {"value": round(len(dumped) * 4 * d / (t1 - t0) / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the oracle's dump + update of all {len(dumped)} cached rows, rows already in memory (no lower-tier lookup)"}
+        oc.close()
     torch.cuda.synchronize()
     B.hps_cache_destroy(h)
     B.hps_hostmap_destroy(hm)
@@ -488,12 +676,43 @@ def multi_table(a, np, torch, B, inputs):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / (reps * nb)
     hit = 1.0 - float(nm.cpu().numpy().mean()) / n
-    alg = 8 * n + (64 + 4 * d) * n * hit * 0.5 + 4 * d * n * hit          # rough: half of the hit keys distinct
+    # algorithmic bytes of one launch, exactly: the query formula per table on the realised batch 0
+    B.hps_cache_query_multi(hs, keys[0], Bn, outs[0], mi, mk, nm[0:1])
+    torch.cuda.synchronize()
+    m0 = int(nm[0].item())
+    midx = np.sort(mi[:m0].cpu().numpy().view(np.uint32).astype(np.int64))
+    hk = keys[0].cpu().numpy()
+    alg = 0
+    for t in range(26):
+        mt = midx[(midx >= t * Bn) & (midx < (t + 1) * Bn)] - t * Bn
+        alg += query_alg_bytes(np, hk[t], mt, d) - 4
+    alg += 4
     res = {"metric": "multi-table lookup Mkeys/s (26 tables, one launch)", "value": round(n / (ms * 1e-3) / 1e6, 1),
            "unit": "Mkeys/s", "n_gpus": 1, "steps": reps * nb, "warmup": nb, "ms_per_step": round(ms, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
            "config": {"workload": f"26 caches, slots {min(slots)}..{max(slots)} (total {sum(slots)}), dim {d}, batch {Bn} samples x 26 keys",
-                      "hit_rate": round(hit, 4), "out_write_GBps": round(n * hit * 4 * d / (ms * 1e-3) / 1e9, 1)}}
+                      "hit_rate": round(hit, 4), "out_write_GBps": round(n * hit * 4 * d / (ms * 1e-3) / 1e9, 1)},
+           "roofline": roofline_obj("query_kernel<ways=8, checked=False>, 26 tables in one launch", alg, ms * 1e3)}
+    if not a.no_cpu_baseline:
+        # the oracle's 26 caches, filled the same way, queried table by table on batch 0
+        from oracle import OracleCache
+        filler = np.random.Generator(np.random.PCG64(0)).integers(0, 1 << 32, size=(1 << 18, d), dtype=np.uint32)
+        ocs = []
+        for sl in slots:
+            oc = OracleCache(sl, W, d)
+            for hi in range(sl, 0, -(1 << 18)):
+                lo = max(0, hi - (1 << 18))
+                oc.insert(np.arange(hi - 1, lo - 1, -1, dtype=np.int64), filler[: hi - lo])
+            ocs.append(oc)
+        out_cpu = np.empty((Bn, d), dtype=np.uint32)
+        t0 = time.perf_counter()
+        for t, oc in enumerate(ocs):
+            oc.query(hk[t], out_cpu)
+        t1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(n / (t1 - t0) / 1e6, 2), "unit": "Mkeys/s", "cores": 1, "kind": "oracle",
+                               "sample": "one batch of 131072 samples x 26 tables, the oracle's caches prefilled in the same order"}
+        for oc in ocs:
+            oc.close()
     torch.cuda.synchronize()
     for h in hs:
         B.hps_cache_destroy(h)
@@ -546,6 +765,10 @@ def concurrent(a, np, torch, B, inputs):
     reps = max(1, a.steps // nb)
     q_alone, u_alone, both = run(True, False, reps), run(False, True, reps) / 2, run(True, True, reps)
     hit = 1.0 - float(nm.cpu().numpy().mean()) / n_q
+    B.hps_cache_query(h, qk[0], n_q, outs[0], mi, mk, nm[0:1], qs)
+    torch.cuda.synchronize()
+    m0 = int(nm[0].item())
+    alg_q = query_alg_bytes(np, qk[0].cpu().numpy(), mi[:m0].cpu().numpy().view(np.uint32), d)
     res = {"metric": "query Mkeys/s while updates run on a second stream", "value": round(n_q / (both * 1e-3) / 1e6, 1),
            "unit": "Mkeys/s", "n_gpus": 1, "steps": reps * nb, "warmup": nb, "ms_per_step": round(both, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
@@ -553,7 +776,26 @@ def concurrent(a, np, torch, B, inputs):
                       "hit_rate": round(hit, 4), "query_alone_ms": round(q_alone, 4), "update_batch_alone_ms": round(u_alone, 4),
                       "query_plus_2_updates_overlapped_ms": round(both, 4),
                       "query_alone_Mkeys_s": round(n_q / (q_alone * 1e-3) / 1e6, 1),
-                      "update_alone_Mpairs_s": round(n_u / (u_alone * 1e-3) / 1e6, 1)}}
+                      "update_alone_Mpairs_s": round(n_u / (u_alone * 1e-3) / 1e6, 1)},
+           "roofline": roofline_obj("query_kernel<ways=8, checked=True>, alone on its stream", alg_q, q_alone * 1e3),
+           "roofline_update": roofline_obj("update_kernel<8,64>, alone on its stream (half of the keys cached)",
+                                           n_u * (8 + 64) + (n_u // 2) * (2 * 4 * d + 8), u_alone * 1e3)}
+    if not a.no_cpu_baseline:
+        # the oracle on a scaled-down geometry (2^21 sets instead of 2^24: the full one needs 64 GiB of host rows),
+        # the same query keys folded into its id range, one query batch and one update batch
+        oc, filler = oracle_hot_cache(np, (1 << 21) * W, W, d)
+        kq = qk[0].cpu().numpy() % (1 << 25)
+        ku = uk[0].cpu().numpy() % (1 << 25)
+        out_cpu = np.empty((n_q, d), dtype=np.uint32)
+        t0 = time.perf_counter()
+        oc.query(kq, out_cpu)
+        t1 = time.perf_counter()
+        oc.update(ku, filler[:n_u] if len(filler) >= n_u else np.resize(filler, (n_u, d)))
+        t2 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(n_q / (t1 - t0) / 1e6, 2), "unit": "Mkeys/s", "cores": 1, "kind": "oracle",
+                               "sample": (f"one query batch of {n_q} keys against a cache of 2^21 sets (an eighth of the workload's), "
+                                          f"then one update batch: {round(n_u / (t2 - t1) / 1e6, 2)} Mpairs/s")}
+        oc.close()
     torch.cuda.synchronize()
     B.hps_cache_destroy(h)
     print(json.dumps(res))
@@ -705,24 +947,20 @@ def main():
     alg = []
     distinct_frac = []
     for b in stat_b:
-        kb = host_keys[b]
         m = int(nm[b].item())
         midx = mi[b][:m].cpu().numpy().view(np.uint32)
-        D = np.unique(kb).size
-        D_m = np.unique(kb[midx]).size
-        D_h = D - D_m
-        n_h = n - m
-        alg.append(8 * n + 64 * D + 4 * d * D_h + 4 * d * n_h + 12 * m + 4)
-        distinct_frac.append(D / n)
+        alg.append(query_alg_bytes(np, host_keys[b], midx, d))
+        distinct_frac.append(np.unique(host_keys[b]).size / n)
     alg_bytes = float(np.mean(alg))
-    achieved = alg_bytes / (ms_per_step * 1e-3) / 1e9
     hit_rate = 1.0 - float(n_miss.mean()) / n
 
-    traffic = None
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "query_c2_traffic.json")
-    if a.keys == "zipf" and os.path.exists(tpath):
+    if a.keys == "zipf" and os.path.exists(tpath) and not a.coherent and n == 106496:
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            traffic_source = ("recorded earlier with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/query_c2_traffic.json), "
+                              "not measured in this run")
         except Exception:
             traffic = None
 
@@ -733,6 +971,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    kernel_name = f"query_kernel<ways={W}, checked={bool(a.coherent)}>"
     result = {
         "metric": METRIC, "value": round(mkeys, 1), "unit": "Mkeys/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -744,15 +983,10 @@ def main():
             "hit_rate": round(hit_rate, 4), "distinct_key_fraction": round(float(np.mean(distinct_frac)), 4),
             "out_buffers_rotated": a.out_buffers, "concurrent_writer_checks": bool(a.coherent),
             "replacement_policy": a.policy,
-            "launch": "hip graph" if graph is not None else "eager, one call per batch",
+            "launch": "hip graph" if graph is not None else "eager, one call per batch, one stream",
             "repeat_ms": [round(t, 3) for t in times],
         },
-        "roofline": {
-            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-            "kernel": f"query_kernel<ways={W}, checked={bool(a.coherent)}>", "algorithmic_bytes_per_launch": round(alg_bytes),
-            "us_per_launch": round(ms_per_step * 1e3, 3),
-        },
+        "roofline": roofline_obj(kernel_name, alg_bytes, ms_per_step * 1e3, traffic, traffic_source=traffic_source),
     }
 
     if multi is not None:
@@ -760,15 +994,62 @@ def main():
         multi["frac_of_peak"] = round(multi["achieved_GBps"] / HBM_PEAK_GBS, 4)
         result["concurrent_streams"] = multi
 
+    # ---- the same batches, several per launch (one launch for k consecutive batches through the
+    #      multi-table entry point with the one cache named k times): what a caller with a queue
+    #      of batches gets; the launch floor is paid once per k batches
+    if a.batched > 1 and not a.coherent and graph is None:
+        k = a.batched
+        handles = (C.c_void_p * k)(*[h] * k)
+        big_outs = [torch.empty(k * n, d, dtype=torch.float32, device="cuda") for _ in range(max(2, 16 // k))]
+        bmi = torch.empty(k * n, dtype=torch.int32, device="cuda")
+        bmk = torch.empty(k * n, dtype=torch.int64, device="cuda")
+        bnm = torch.zeros(n_batches, dtype=torch.int32, device="cuda")
+        qm = lib.hps_cache_query_multi
+        groups = [b for b in range(a.warmup, n_batches - k + 1, k)]
+
+        def launch_group(gi):
+            b = groups[gi % len(groups)]
+            r = qm(handles, k, kp + b * n * 8, n, big_outs[gi % len(big_outs)].data_ptr(), bmi.data_ptr(), bmk.data_ptr(),
+                   bnm.data_ptr() + b * 4, sp)
+            if r != 0:
+                raise RuntimeError(B.hps_last_error())
+
+        cnt = [0]
+
+        def one():
+            launch_group(cnt[0])
+            cnt[0] += 1
+        us = event_us(torch, one, len(groups) * 3, warm=len(groups))
+        got = int(bnm[groups[0]].item())
+        want = int(nm[groups[0]:groups[0] + k].sum().item())
+        assert got == want, (got, want)                       # same misses as the k single launches
+        result["batched_launch"] = {"batches_per_launch": k, "us_per_batch": round(us / k, 3),
+                                    "value": round(n / (us / k) , 1), "unit": "Mkeys/s",
+                                    "frac_of_peak": round(alg_bytes / (us / k * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+        del big_outs
+
+    # ---- the library's default mode (queries validate rows against concurrent writers), same batches
+    if not a.coherent and graph is None and a.also_checked:
+        B.hps_cache_set_concurrent_writers(h, True)
+        cnt = [0]
+
+        def one_checked():
+            launch(a.warmup + cnt[0] % a.steps)
+            cnt[0] += 1
+        us = event_us(torch, one_checked, a.steps, warm=20)
+        B.hps_cache_set_concurrent_writers(h, False)
+        result["checked_query"] = {"what": "same batches with hps_cache_set_concurrent_writers(1), the library default",
+                                   "us_per_launch": round(us, 3), "value": round(n / us, 1), "unit": "Mkeys/s",
+                                   "frac_of_peak": round(alg_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ---- ceiling: the row movement of the same batches with nothing else (slots given, no hash,
+    #      no probe, no miss list), and a plain streaming copy of the same number of bytes
+    if a.ceiling and graph is None and a.keys == "zipf":
+        result["roofline"].update(measure_ceiling(a, np, torch, B, h, host_keys, keys, mi, nm, outs, n, d, S, W, alg_bytes))
+
     # ---- CPU oracle on the host cores, bounded sample of the same batches
     if not a.no_cpu_baseline:
-        from oracle import OracleCache
-        oc = OracleCache(slots, W, d)
-        rng = np.random.Generator(np.random.PCG64(0))
-        filler = rng.integers(0, 1 << 32, size=(chunk, d), dtype=np.uint32)   # row content is irrelevant to timing
-        for hi in range(slots, 0, -chunk):
-            lo = max(0, hi - chunk)
-            oc.insert(np.arange(hi - 1, lo - 1, -1, dtype=np.int64), filler[: hi - lo])
+        oc, _ = oracle_hot_cache(np, slots, W, d, chunk)
         nb = min(a.cpu_batches, a.steps)
         sample = host_keys[a.warmup:a.warmup + nb]
         out_cpu = np.empty((n, d), dtype=np.uint32)
@@ -811,6 +1092,76 @@ def main():
     B.hps_cache_destroy(h)
     result["config"]["setup_seconds"] = round(time.time() - t_setup, 1)
     print(json.dumps(result))
+
+
+def measure_ceiling(a, np, torch, B, h, host_keys, keys, mi, nm, outs, n, d, S, W, alg_bytes):
+    """What the memory system gives for the byte movement of the timed query batches alone.
+    The slot of every hit position is looked up on the host in the exported key array; then
+    hps_membench_gather moves exactly the rows the query moved (its output is compared with the
+    query's), launched the same way on the same rotating `out` buffers."""
+    slots = S * W
+    nb = min(32, a.steps)
+    gk = torch.empty(slots, dtype=torch.int64, device="cuda")
+    gc = torch.empty(S, dtype=torch.int32, device="cuda")
+    gv = torch.empty(slots, d, dtype=torch.float32, device="cuda")
+    B.hps_cache_export(h, gk, gc, gv)
+    torch.cuda.synchronize()
+    hk = gk.cpu().numpy()
+    order = np.argsort(hk, kind="stable")
+    sk = hk[order]
+    slot_of = np.empty((nb, n), dtype=np.uint32)
+    for i in range(nb):
+        kb = host_keys[a.warmup + i]
+        pos = np.clip(np.searchsorted(sk, kb), 0, slots - 1)
+        found = sk[pos] == kb
+        slot_of[i] = np.where(found, order[pos], 0xFFFFFFFF).astype(np.uint32)
+        m = int(nm[a.warmup + i].item())
+        assert int((~found).sum()) == m                   # the same positions miss
+    d_slot = torch.from_numpy(slot_of.view(np.int32)).cuda()
+    # the gather moves what the query moved: compare one batch bit for bit
+    ref = torch.zeros(n, d, dtype=torch.float32, device="cuda")
+    got = torch.zeros(n, d, dtype=torch.float32, device="cuda")
+    nm1 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    mi1 = torch.empty(n, dtype=torch.int32, device="cuda")
+    mk1 = torch.empty(n, dtype=torch.int64, device="cuda")
+    B.hps_cache_query(h, keys[a.warmup], n, ref, mi1, mk1, nm1)
+    B.hps_membench_gather(gv, d_slot[0], n, d, got)
+    torch.cuda.synchronize()
+    assert torch.equal(ref.view(torch.int32), got.view(torch.int32))
+    cnt = [0]
+
+    def one():
+        i = cnt[0]
+        B.hps_membench_gather(gv, d_slot[i % nb], n, d, outs[i % len(outs)])
+        cnt[0] += 1
+    us_gather = event_us(torch, one, a.steps, warm=20)
+    # a streaming copy that reads and writes as many bytes as the query's algorithmic figure
+    half = int(alg_bytes // 2) // 4096 * 4096
+    src = torch.empty(16 * half // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty(16 * half // 4, dtype=torch.float32, device="cuda")
+    cnt2 = [0]
+
+    def copy_one():
+        o = (cnt2[0] % 16) * (half // 4)
+        B.hps_membench_copy(src[o:], dst[o:], half, True)
+        cnt2[0] += 1
+    us_copy = event_us(torch, copy_one, a.steps, warm=20)
+    big = 1 << 30
+    bsrc = torch.empty(big // 4, dtype=torch.float32, device="cuda")
+    bdst = torch.empty(big // 4, dtype=torch.float32, device="cuda")
+    us_big = event_us(torch, lambda: B.hps_membench_copy(bsrc, bdst, big, True), 10, warm=2)
+    del gk, gc, gv, src, dst, bsrc, bdst
+    return {
+        "achievable_frac": round(alg_bytes / (us_gather * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        "ceiling": {
+            "what": ("hps_membench_gather: out[i] = rows[slot[i]] for the hit positions of the same batches (slots "
+                     "precomputed; no hashing, probing or miss list), one launch per batch on the same stream and the same "
+                     "rotating out buffers; output equal to the query's"),
+            "gather_us_per_launch": round(us_gather, 3),
+            "streaming_copy_of_the_same_bytes_us_per_launch": round(us_copy, 3),
+            "streaming_copy_1GiB_GBps_read_plus_write": round(2 * big / (us_big * 1e-6) / 1e9, 1),
+        },
+    }
 
 
 if __name__ == "__main__":
