@@ -67,7 +67,7 @@ def parse():
     p.add_argument("--no-ceiling", dest="ceiling", action="store_false",
                    help="skip the ceiling measurement (row gather with given slots, streaming copy)")
     p.add_argument("--calibrate-copy", action="store_true",
-                   help="also run one plain 1 GiB device copy (reference for the rocprofv3 byte counters)")
+                   help="also run one plain 1 GiB device copy, membench_copy_kernel (reference for the rocprofv3 byte counters)")
     return p.parse_args()
 
 
@@ -967,7 +967,7 @@ def main():
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        B.hps_membench_copy(src, dst, 1 << 30, False)        # 1 GiB read + 1 GiB written, plain loads and stores
         torch.cuda.synchronize()
         del src, dst
 
