@@ -142,63 +142,48 @@ struct RowGeom {
 
 // Copy `cnt` (> 0) rows listed in LDS: row srcRow[e] of `src` to row dstRow[e] of `dst`, for
 // e < cnt.  LPR lanes move one row, 16 B per lane, so a wave load/store covers 64/LPR whole
-// rows.  Two register buffers of U wave loads each alternate: the loads of the next group are
-// issued before the stores of the current one, so a wave always has loads in flight while it
-// stores (measured on the 106,496-key hot-cache batch: 21.5 us with 2 x 2 wave loads against
-// 22.9 us with one buffer of 4).  The code is branch-free inside a group: lanes beyond the list
-// (or beyond the row, when d/4 is not a power of two) repeat entry 0 / chunk 0, i.e. they store
-// the same bytes to the same place as a live lane, and the loads issued past the last group
-// re-read entry 0 and are dropped.
-//
-// kTwoBuffers = false is the same loop with one buffer (load U, store U): batches of 2^18 keys and
-// more, whose work-groups run several to a CU, measured 5 % faster with one buffer of 8.
-template <int U, bool kTwoBuffers = true, typename SrcIdx, typename DstIdx>
+// rows.  The rows go in groups of U wave loads, and a group's loads are ALL issued before its
+// first store (each store then waits only for its own load): with U = 26 the 52 rows of a wave
+// of the 106,496-key batch (two 512-byte rows per wave load) are one group, every worker wave has
+// its whole share of the batch in flight at once, and the launch takes 18.4 us in the stand-alone
+// test bed against 21.5 us with two alternating buffers of 2 wave loads and 22.9 us with one
+// buffer of 4 (two groups of 15: 20.3 us).  Non-temporal loads here cost 6 us (repeated keys live
+// on L2 hits), non-temporal stores save 2 us (rows of `out` are written once and not read again
+// here).  Lanes beyond the list load entry 0 and store nothing; lanes beyond the row (d/4 not a
+// power of two) repeat chunk 0.
+// kD = 128 fixes the row geometry at compile time (32 lanes per row, one pass, shifts instead
+// of multiplications); kD = 0 takes it from g.
+template <int U, int kD = 0, typename SrcIdx, typename DstIdx>
 __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restrict__ src,
                                           float *__restrict__ dst, const SrcIdx *srcRow,
                                           const DstIdx *dstRow, uint32_t cnt) {
+    static_assert(kD == 0 || kD == 128, "only the 128-word row is specialised");
     const uint32_t lane = (uint32_t)lane_id();
-    const uint32_t rpi = (uint32_t)kWave >> g.lprShift;      // rows per wave load
-    const uint32_t sub = lane >> g.lprShift;                 // which of those rows this lane serves
-    const uint32_t cl  = lane & (g.LPR - 1);                 // chunk of the row this lane moves
-    const uint32_t step = rpi * U;
-    for (uint32_t pass = 0; pass < g.passes; ++pass) {
-        uint32_t chunk = cl + pass * g.LPR;
-        chunk = chunk < g.C ? chunk : 0u;
+    const uint32_t lprShift = kD ? 5u : g.lprShift;
+    const uint32_t LPR = kD ? 32u : g.LPR;
+    const uint32_t C = kD ? 32u : g.C;
+    const uint64_t d = kD ? (uint64_t)kD : (uint64_t)g.d;
+    const uint32_t passes = kD ? 1u : g.passes;
+    const uint32_t rpi = (uint32_t)kWave >> lprShift;        // rows per wave load
+    const uint32_t sub = lane >> lprShift;                   // which of those rows this lane serves
+    const uint32_t cl  = lane & (LPR - 1);                   // chunk of the row this lane moves
+    for (uint32_t pass = 0; pass < passes; ++pass) {
+        uint32_t chunk = cl + pass * LPR;
+        chunk = chunk < C ? chunk : 0u;
         const uint32_t off = chunk * 4;
-        f32x4 bufA[U], bufB[U];
-        uint64_t dpA[U], dpB[U];
-        auto load = [&](uint32_t e0, f32x4 (&buf)[U], uint64_t (&dp)[U]) {
+        for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
+            f32x4 buf[U];
+            uint32_t ent[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                uint32_t e = e0 + u * rpi + sub;
-                e = e < cnt ? e : 0u;
-                dp[u] = (uint64_t)dstRow[e];
-                buf[u] = *reinterpret_cast<const f32x4 *>(src + (uint64_t)srcRow[e] * g.d + off);
+                const uint32_t e = e0 + u * rpi + sub;
+                ent[u] = e < cnt ? e : 0xFFFFFFFFu;
+                buf[u] = *reinterpret_cast<const f32x4 *>(src + (uint64_t)srcRow[e < cnt ? e : 0u] * d + off);
             }
-        };
-        auto store = [&](const f32x4 (&buf)[U], const uint64_t (&dp)[U]) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                // non-temporal: rows of `out` are written once and not read again here (24.9 us per
-                // 106,496-key batch with plain stores against 22.9 us)
-                __builtin_nontemporal_store(buf[u], reinterpret_cast<f32x4 *>(dst + dp[u] * g.d + off));
-            }
-        };
-        if (kTwoBuffers) {
-            load(0, bufA, dpA);
-            for (uint32_t e0 = 0;; e0 += 2 * step) {
-                load(e0 + step, bufB, dpB);
-                store(bufA, dpA);
-                if (e0 + step >= cnt) break;
-                load(e0 + 2 * step, bufA, dpA);
-                store(bufB, dpB);
-                if (e0 + 2 * step >= cnt) break;
-            }
-        } else {
-            for (uint32_t e0 = 0; e0 < cnt; e0 += step) {
-                load(e0, bufA, dpA);
-                store(bufA, dpA);
-            }
+            for (int u = 0; u < U; ++u)
+                if (ent[u] != 0xFFFFFFFFu)
+                    __builtin_nontemporal_store(buf[u], reinterpret_cast<f32x4 *>(dst + (uint64_t)dstRow[ent[u]] * d + off));
         }
     }
 }
@@ -252,39 +237,44 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
         }
         return;
     }
-    const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;
+    // Rows of up to 1 KiB: the wave's rows go in groups of U wave loads (one group when U covers
+    // the list, which the launch shapes arrange), all of a group's loads in flight together; then
+    // ONE more wave load reads the sequence words again, lane l that of the group's row l, and a
+    // ballot of "changed" gives the rows to redo.  Two dependent round trips per group, so the
+    // fewer groups the better (27.5 us per 106,496-key batch with groups of 16 rows, 21.6 us with one).
+    const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;    // rows per wave load
     const uint32_t sub = lane >> g.lpr8Shift;
     const uint32_t cl  = lane & (g.LPR8 - 1);
-    const uint64_t grp = (g.LPR8 == 64 ? ~0ull : ((1ull << g.LPR8) - 1)) << (sub << g.lpr8Shift);
     const uint32_t chunk = cl < g.C8 ? cl : 0u;
-    for (uint32_t e0 = 0; e0 < cnt; e0 += rpi * U) {
+    const uint32_t span = rpi * U < (uint32_t)kWave ? rpi * U : (uint32_t)kWave;   // rows per group: one validating lane each
+    for (uint32_t e0 = 0; e0 < cnt; e0 += span) {
+        const uint32_t rows = cnt - e0 < span ? cnt - e0 : span;
         uint64_t buf[U];
-        uint32_t ent[U];
-        bool real[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t e = e0 + u * rpi + sub;
-            real[u] = e < cnt;
-            ent[u] = real[u] ? e : 0u;
-            buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[ent[u]] * g.d) + chunk);
-        }
-        shared_acquire();                                       // row loads complete before the re-read
-        uint32_t v2[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v2[u] = ld_agent(sc + 2ull * setOf[ent[u]]);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            // One verdict per row: every lane of the row's group must have seen the unchanged
-            // word (the ballot makes the lanes of a group agree even if their loads did not).
-            const uint64_t bad = __ballot(v2[u] != v1Of[ent[u]]);
-            const bool ok = (bad & grp) == 0;
-            if (real[u] && ok) {
-                __builtin_nontemporal_store(
-                    buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[ent[u]] * g.d) + chunk);
-            } else if (real[u] && cl == 0) {
-                __hip_atomic_fetch_or(retry + (ent[u] >> 5), 1u << (ent[u] & 31), __ATOMIC_RELAXED,
-                                      __HIP_MEMORY_SCOPE_WORKGROUP);
+            if ((uint32_t)u * rpi < rows) {                          // uniform: this wave load has rows to fetch
+                uint32_t r = (uint32_t)u * rpi + sub;
+                r = r < rows ? r : 0u;
+                buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[e0 + r] * g.d) + chunk);
             }
+        }
+        shared_acquire();                                            // row loads complete before the re-read
+        const bool mine = lane < rows;
+        const uint32_t v2 = mine ? ld_agent(sc + 2ull * setOf[e0 + lane]) : 0u;
+        const uint64_t bad = __ballot(mine && v2 != v1Of[e0 + lane]);   // bit r: row e0 + r was touched by a writer
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if ((uint32_t)u * rpi < rows) {
+                const uint32_t r = (uint32_t)u * rpi + sub;
+                if (r < rows && !((bad >> r) & 1ull))
+                    __builtin_nontemporal_store(
+                        buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[e0 + r] * g.d) + chunk);
+            }
+        }
+        if (bad && lane == 0) {                                      // span <= 64 and e0 is a multiple of it
+            const uint64_t m = bad << (e0 & 63u);
+            __hip_atomic_fetch_or(retry + 0, (uint32_t)m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_or(retry + 1, (uint32_t)(m >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 }
@@ -417,7 +407,7 @@ __device__ __forceinline__ void finish_call(const QueryArgs &a, uint32_t n_miss,
 // (odd word), copies rows with copy_rows_checked and repeats for the keys whose set changed under
 // it.  A miss needs no check (an 8-byte key is read whole, and a key that stays cached is never
 // absent from its slot), so only hits are validated.
-template <int W, int KPW, int U, int WPB, bool kCoherent, bool kTwoBuffers = true>
+template <int W, int KPW, int U, int WPB, bool kCoherent, int kD = 0>
 __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArgs a) {
     __shared__ uint64_t s_src[WPB][KPW];
     __shared__ uint32_t s_dst[WPB][KPW];
@@ -531,7 +521,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                 }
                 wave_lds_fence();
                 if (lane == 0) __hip_atomic_fetch_add(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (nh) copy_rows<U, kTwoBuffers>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
+                if (nh) copy_rows<U, kD>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], nh);
             }
         } else {
             if (kCoherent) {
@@ -1083,7 +1073,7 @@ __global__ void backing_kernel(const int64_t *__restrict__ keys, uint32_t n,
 
 // The row movement of query_kernel's plain variant alone: same tile shape, same copy loop, but the
 // source slot of every position is given, so nothing is hashed, probed or compacted.
-template <int U, int WPB>
+template <int U, int WPB, int kD>
 __global__ void __launch_bounds__(WPB * kWave) membench_gather_kernel(const float *__restrict__ rows,
                                                                       const uint32_t *__restrict__ slot_of, uint32_t n,
                                                                       uint32_t kpw, const RowGeom g, float *__restrict__ out) {
@@ -1103,7 +1093,7 @@ __global__ void __launch_bounds__(WPB * kWave) membench_gather_kernel(const floa
         s_dst[wave][r] = pos;
     }
     wave_lds_fence();
-    if (nh) copy_rows<U>(g, rows, out, &s_src[wave][0], &s_dst[wave][0], nh);
+    if (nh) copy_rows<U, kD>(g, rows, out, &s_src[wave][0], &s_dst[wave][0], nh);
 }
 
 template <int U, bool kNT>
@@ -1214,38 +1204,64 @@ uint64_t *counter_word(hps_cache *c, void *stream) {
     return c->ring + it->second;
 }
 
-// Launch shape of the query kernel: KPW keys per worker wave, two register buffers of U wave loads
-// each in the row copy, WPB worker waves per work-group.  Chosen from the batch size (measured on 256 CUs with 512-byte rows):
-// small batches want many small work-groups, ~10^5 keys want 512-key tiles (half as many
-// same-address counter atomics, which cost ~11 ns each and serialise), large batches want
-// more loads in flight.
+// Launch shape of the query kernel: KPW keys per worker wave, row copy in groups of U wave loads,
+// WPB worker waves per work-group.  Chosen from the batch size (measured on 256 CUs with 512-byte
+// rows): small batches want many small work-groups, ~10^5 keys want 512-key tiles (half as many
+// same-address counter atomics, which cost ~11 ns each and serialise).  U is large enough for a
+// wave's whole share of 512-byte rows to be one group (26 wave loads for the 52 keys per wave of
+// the 106,496-key batch, 32 for 64 keys per wave).
 struct QueryShape { int kpw, u, wpb; };
 
-QueryShape query_shape(uint64_t n) {
-    if (n < (1u << 16)) return QueryShape{64, 2, 4};      // two buffers of 2 wave loads
-    if (n < (1u << 18)) return QueryShape{64, 2, 8};      // two buffers of 2 wave loads
-    return QueryShape{64, 8, 4};                          // one buffer of 8 wave loads
+QueryShape query_shape(uint64_t n, bool coherent) {
+    if (coherent) {
+        // The checked variant reads rows 8 bytes per lane (one 512-byte row per wave load) and pays two
+        // dependent round trips per group (rows, then the sequence words again), so a wave's rows
+        // should be ONE group: 64 keys per wave need 128 data registers, which 8 waves per
+        // work-group (2 per SIMD, 256 registers each) leave room for and 9 do not.  Measured in the
+        // stand-alone test bed on the 106,496-key batch: groups of 16 rows, 9 waves 27.5 us; groups
+        // of 32, 8 waves 23.1 us; one group, 8 waves 21.6 us.
+        if (n < (1u << 16)) return QueryShape{64, 64, 4};
+        if (n < (1u << 18)) return QueryShape{64, 64, 7};
+        return QueryShape{64, 64, 4};
+    }
+    if (n < (1u << 16)) return QueryShape{64, 26, 4};
+    if (n < (1u << 18)) return QueryShape{64, 26, 8};
+    return QueryShape{64, 32, 4};
 }
 
 template <int W, int KPW, int U, int WPB>
-void launch_query_shape(const QueryArgs &a, bool coherent, bool dedup, hipStream_t st) {
-    constexpr bool kTwo = U < 8;
+void launch_query_plain(const QueryArgs &a, bool dedup, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
-    if (coherent) hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true>), dim3(grid), block, 0, st, a);
-    else if (dedup && KPW == kWave)
-        hipLaunchKernelGGL((query_dedup_kernel<W, (kTwo ? 2 * U : U), WPB>), dim3(grid), block, 0, st, a);
-    else hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, kTwo>), dim3(grid), block, 0, st, a);
+    if (dedup && KPW == kWave)
+        hipLaunchKernelGGL((query_dedup_kernel<W, (WPB == 8 ? 4 : 8), WPB>), dim3(grid), block, 0, st, a);
+    else if (a.g.d == 128) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, 128>), dim3(grid), block, 0, st, a);
+    else   // any other row width: run-time row geometry needs more registers, so smaller groups under the 9-wave limit
+        hipLaunchKernelGGL((query_kernel<W, KPW, (WPB == 8 ? 16 : U), WPB, false, 0>), dim3(grid), block, 0, st, a);
+}
+
+template <int W, int KPW, int U, int WPB>
+void launch_query_checked(const QueryArgs &a, hipStream_t st) {
+    const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
+    hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, true>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
 }
 
 template <int W>
 hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, bool dedup, hipStream_t st) {
     const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
-    switch (id) {
-        case 640204: launch_query_shape<W, 64, 2, 4>(a, coherent, dedup, st); break;
-        case 640208: launch_query_shape<W, 64, 2, 8>(a, coherent, dedup, st); break;
-        case 640804: launch_query_shape<W, 64, 8, 4>(a, coherent, dedup, st); break;
-        default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
+    if (coherent) {
+        switch (id) {
+            case 646404: launch_query_checked<W, 64, 64, 4>(a, st); break;
+            case 646407: launch_query_checked<W, 64, 64, 7>(a, st); break;
+            default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
+        }
+    } else {
+        switch (id) {
+            case 642604: launch_query_plain<W, 64, 26, 4>(a, dedup, st); break;
+            case 642608: launch_query_plain<W, 64, 26, 8>(a, dedup, st); break;
+            case 643204: launch_query_plain<W, 64, 32, 4>(a, dedup, st); break;
+            default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
+        }
     }
     HIP_TRY(hipGetLastError());
     return HPS_OK;
@@ -1472,7 +1488,9 @@ static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, co
     a.slot = counter_word(caches[0], stream);
     a.B = (uint32_t)batch;
     a.n_dev = n_dev;
-    const QueryShape shape = query_shape(total);
+    bool coherent = false;                      // any table that may see concurrent writers makes the call careful
+    for (uint32_t t = 0; t < n_tables; ++t) coherent = coherent || caches[t]->concurrent_writers.load() != 0;
+    const QueryShape shape = query_shape(total, coherent);
     // Keys per worker wave: at most 64, trimmed so that the work-groups come out as a whole number
     // of rounds over the CUs (106,496 keys in tiles of 8 x 52 are exactly 256 work-groups; tiles of
     // 8 x 64 would be 208, leaving 48 CUs idle).  Small batches go down to 16 keys per wave (8 below
@@ -1496,8 +1514,6 @@ static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, co
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
     a.g = make_geom(caches[0]->d);
-    bool coherent = false;                      // any table that may see concurrent writers makes the call careful
-    for (uint32_t t = 0; t < n_tables; ++t) coherent = coherent || caches[t]->concurrent_writers.load() != 0;
     const bool dedup = caches[0]->query_dedup.load() != 0;
     return launch_query(caches[0]->W, a, shape, coherent, dedup, static_cast<hipStream_t>(stream));
 }
@@ -1630,8 +1646,12 @@ hps_status_t hps_membench_gather(const float *rows, const uint32_t *slot_of, siz
     const uint64_t tile = kpw * kWpb;
     const uint64_t blocks = (n + tile - 1) / tile;
     if (blocks >= (1ull << 31)) return fail(HPS_ERR_INVALID_ARG, "n too large");
-    hipLaunchKernelGGL((membench_gather_kernel<2, kWpb>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0,
-                       static_cast<hipStream_t>(stream), rows, slot_of, (uint32_t)n, (uint32_t)kpw, make_geom(dim), out);
+    if (dim == 128)
+        hipLaunchKernelGGL((membench_gather_kernel<26, kWpb, 128>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0,
+                           static_cast<hipStream_t>(stream), rows, slot_of, (uint32_t)n, (uint32_t)kpw, make_geom(dim), out);
+    else
+        hipLaunchKernelGGL((membench_gather_kernel<26, kWpb, 0>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0,
+                           static_cast<hipStream_t>(stream), rows, slot_of, (uint32_t)n, (uint32_t)kpw, make_geom(dim), out);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
