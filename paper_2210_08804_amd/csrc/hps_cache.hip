@@ -44,8 +44,8 @@ constexpr uint64_t kMagic      = 0x4850534341434845ull;
 // rounds (a held set is released within microseconds; this many rounds take about a second) and
 // raises HPS_FLAG_STUCK_SET in the cache's flag word, so that no wave can spin forever.
 constexpr uint32_t kMaxRounds  = 1u << 16;
-// Longest row (in fp32) that a query may read while writers run: such a row is staged whole in LDS
-// (one row per worker wave) before it is validated and stored.
+// Longest row (in fp32) that a query may read while writers run: a row is read whole (8 wave loads
+// of 8 bytes per lane at this length) before it is validated and stored.
 constexpr uint32_t kMaxCheckedDim = 1024;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk of a row
@@ -194,68 +194,50 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
 // read again once those loads have completed; a row is stored only if its word is unchanged,
 // i.e. no writer touched the set while the row was being read.  Entries to redo are flagged in
 // the LDS word pair `retry`.
-// Rows of up to 1 KiB fit one wave load (8 bytes x 64 lanes x 2 rows at most), so a row is
-// validated and stored in one piece.  Longer rows (up to kMaxCheckedDim fp32) go one at a time
-// through `stage`, this wave's LDS buffer of kMaxCheckedDim / 2 8-byte words: the whole row is
-// read, then validated, then stored, so that a position whose key turns out to be gone on the
-// retry (evicted by an overlapping insert) has had nothing written to its `out` row.
-template <int U>
+// The wave's rows go in groups of U wave loads, all of a group's loads in flight together; then
+// ONE more wave load reads the sequence words again, lane l that of the group's row l, and a
+// ballot of "changed" gives the rows to redo.  That is two dependent round trips per group, so
+// the fewer groups the better (27.5 us per 106,496-key batch with groups of 16 rows, 21.6 us with
+// one group per wave in the stand-alone test bed).  A row is always read whole inside one group
+// (rows longer than 512 bytes take several of the group's wave loads; the longest row, 4 KiB, takes
+// 8, which is why U >= 8 and why kMaxCheckedDim is 1024) and stored only after its validation:
+// a position whose key turns out to be gone on the retry (evicted by an overlapping insert) has
+// had nothing written to its `out` row.
+template <int U, int kD = 0, bool kLong = false>
 __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *__restrict__ src,
                                                   float *__restrict__ dst, const uint64_t *srcRow,
                                                   const uint32_t *dstRow, const uint32_t *setOf,
                                                   const uint32_t *v1Of, const uint32_t *sc,
-                                                  uint32_t cnt, uint32_t *retry, uint64_t *stage) {
+                                                  uint32_t cnt, uint32_t *retry) {
+    static_assert(!(kD && kLong), "the compile-time geometry is a short row");
     const uint32_t lane = (uint32_t)lane_id();
-    if (g.passes8 > 1) {
-        constexpr int kInFlight = 8;                                    // wave loads of one row in flight
-        for (uint32_t e = 0; e < cnt; ++e) {
-            const uint64_t *srow = reinterpret_cast<const uint64_t *>(src + srcRow[e] * g.d);
-            for (uint32_t c0 = 0; c0 < g.C8; c0 += kWave * kInFlight) {
-                uint64_t r[kInFlight];
-#pragma unroll
-                for (int k = 0; k < kInFlight; ++k) {
-                    const uint32_t c = c0 + (uint32_t)k * kWave + lane;
-                    r[k] = shared_ld64(srow + (c < g.C8 ? c : 0u));
-                }
-#pragma unroll
-                for (int k = 0; k < kInFlight; ++k) {
-                    const uint32_t c = c0 + (uint32_t)k * kWave + lane;
-                    if (c < g.C8) stage[c] = r[k];
-                }
-            }
-            shared_acquire();                                           // the whole row has been read
-            const uint32_t v2 = ld_agent(sc + 2ull * setOf[e]);
-            const bool ok = __ballot(v2 != v1Of[e]) == 0;               // one verdict for the wave
-            wave_lds_fence();
-            if (ok) {
-                uint64_t *drow = reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[e] * g.d);
-                for (uint32_t c = lane; c < g.C8; c += kWave) __builtin_nontemporal_store(stage[c], drow + c);
-            } else if (lane == 0) {
-                __hip_atomic_fetch_or(retry + (e >> 5), 1u << (e & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-            wave_lds_fence();                                           // the buffer is reused by the next row
-        }
-        return;
-    }
-    // Rows of up to 1 KiB: the wave's rows go in groups of U wave loads (one group when U covers
-    // the list, which the launch shapes arrange), all of a group's loads in flight together; then
-    // ONE more wave load reads the sequence words again, lane l that of the group's row l, and a
-    // ballot of "changed" gives the rows to redo.  Two dependent round trips per group, so the
-    // fewer groups the better (27.5 us per 106,496-key batch with groups of 16 rows, 21.6 us with one).
-    const uint32_t rpi = (uint32_t)kWave >> g.lpr8Shift;    // rows per wave load
-    const uint32_t sub = lane >> g.lpr8Shift;
-    const uint32_t cl  = lane & (g.LPR8 - 1);
-    const uint32_t chunk = cl < g.C8 ? cl : 0u;
-    const uint32_t span = rpi * U < (uint32_t)kWave ? rpi * U : (uint32_t)kWave;   // rows per group: one validating lane each
+    // Geometry of one wave load of 8 bytes per lane.  Short rows (kLong false, up to 512 bytes):
+    // LPR8 lanes per row, rpi rows per wave load.  Long rows (kLong, up to kMaxCheckedDim fp32):
+    // passes8 wave loads per row.  kD = 128: a 512-byte row is exactly one wave load.
+    // A long row takes 2^pShift >= passes8 of a group's wave loads (those past the row's end are idle).
+    const uint32_t pShift = kLong ? 32u - (uint32_t)__builtin_clz(g.passes8 - 1u) : 0u;
+    const uint32_t rpiShift = (kD || kLong) ? 0u : 6u - g.lpr8Shift;
+    const uint32_t sub = (kD || kLong) ? 0u : lane >> g.lpr8Shift;
+    const uint32_t cl  = (kD || kLong) ? lane : lane & (g.LPR8 - 1);
+    const uint64_t d = kD ? (uint64_t)kD : (uint64_t)g.d;
+    // rows per group: every row of a group is read whole (all its wave loads are among the group's
+    // U), and one lane per row re-reads its sequence word, so a group has at most 64 rows
+    uint32_t span = kLong ? (uint32_t)U >> pShift : (uint32_t)U << rpiShift;
+    span = span < (uint32_t)kWave ? span : (uint32_t)kWave;
     for (uint32_t e0 = 0; e0 < cnt; e0 += span) {
         const uint32_t rows = cnt - e0 < span ? cnt - e0 : span;
         uint64_t buf[U];
+        // wave load u of the group: rows u*rpi .. (short rows), or part u mod 2^pShift of row
+        // u >> pShift (long rows)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if ((uint32_t)u * rpi < rows) {                          // uniform: this wave load has rows to fetch
-                uint32_t r = (uint32_t)u * rpi + sub;
+            const uint32_t r0 = kLong ? (uint32_t)u >> pShift : (uint32_t)u << rpiShift;
+            if (r0 < rows) {                                         // uniform: this wave load has rows to fetch
+                uint32_t r = r0 + sub;
                 r = r < rows ? r : 0u;
-                buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[e0 + r] * g.d) + chunk);
+                uint32_t chunk = kLong ? (((uint32_t)u & ((1u << pShift) - 1u)) << 6) + lane : cl;
+                chunk = chunk < g.C8 || kD ? chunk : 0u;
+                buf[u] = shared_ld64(reinterpret_cast<const uint64_t *>(src + srcRow[e0 + r] * d) + chunk);
             }
         }
         shared_acquire();                                            // row loads complete before the re-read
@@ -264,15 +246,17 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
         const uint64_t bad = __ballot(mine && v2 != v1Of[e0 + lane]);   // bit r: row e0 + r was touched by a writer
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if ((uint32_t)u * rpi < rows) {
-                const uint32_t r = (uint32_t)u * rpi + sub;
-                if (r < rows && !((bad >> r) & 1ull))
+            const uint32_t r0 = kLong ? (uint32_t)u >> pShift : (uint32_t)u << rpiShift;
+            if (r0 < rows) {
+                const uint32_t r = r0 + sub;
+                const uint32_t chunk = kLong ? (((uint32_t)u & ((1u << pShift) - 1u)) << 6) + lane : cl;
+                if (r < rows && (chunk < g.C8 || kD) && !((bad >> r) & 1ull))
                     __builtin_nontemporal_store(
-                        buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[e0 + r] * g.d) + chunk);
+                        buf[u], reinterpret_cast<uint64_t *>(dst + (uint64_t)dstRow[e0 + r] * d) + chunk);
             }
         }
-        if (bad && lane == 0) {                                      // span <= 64 and e0 is a multiple of it
-            const uint64_t m = bad << (e0 & 63u);
+        if (bad && lane == 0) {                                      // e0 + rows <= cnt <= 64
+            const uint64_t m = bad << e0;
             __hip_atomic_fetch_or(retry + 0, (uint32_t)m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             __hip_atomic_fetch_or(retry + 1, (uint32_t)(m >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
@@ -284,7 +268,9 @@ __device__ __forceinline__ void copy_rows_checked(const RowGeom g, const float *
 // Two register buffers alternate: the loads of the next U wave loads are issued before the
 // stores of the current ones, so a write-through store's long acknowledgement never sits between
 // a wave and its next loads.  Lanes past the list repeat entry 0 (same bytes to the same place),
-// and the loads issued past the last group re-read entry 0 and are dropped.
+// and the loads issued past the last group re-read entry 0 and are dropped.  (Groups of 16 or 32
+// wave loads all in flight before the first store, which is what the query's copy does, cost the
+// writers occupancy and time: insert 102 us against 83 us per 2^18 rows, update 118 against 81 us.)
 template <int U>
 __device__ __forceinline__ void copy_rows_shared(const RowGeom g, const float *__restrict__ src,
                                                  float *dst, const uint32_t *srcRow,
@@ -418,7 +404,6 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
     __shared__ uint32_t s_set[kCoherent ? WPB : 1][kCoherent ? KPW : 1];
     __shared__ uint32_t s_v1[kCoherent ? WPB : 1][kCoherent ? KPW : 1];
     __shared__ uint32_t s_retry[kCoherent ? WPB : 1][2];
-    __shared__ uint64_t s_stage[kCoherent ? WPB : 1][kCoherent ? kMaxCheckedDim / 2 : 1];   // rows longer than 1 KiB
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
@@ -477,10 +462,15 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
                         s_v1[wave][r]  = v1;
                     }
                     wave_lds_fence();
-                    if (fmask)
-                        copy_rows_checked<U>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], &s_set[wave][0],
-                                             &s_v1[wave][0], tb.sc, (uint32_t)__popcll(fmask), &s_retry[wave][0],
-                                             &s_stage[wave][0]);
+                    if (fmask) {
+                        const uint32_t nf = (uint32_t)__popcll(fmask);
+                        if (kD != 0 || g.passes8 == 1)
+                            copy_rows_checked<U, kD, false>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], &s_set[wave][0],
+                                                            &s_v1[wave][0], tb.sc, nf, &s_retry[wave][0]);
+                        else
+                            copy_rows_checked<(U > 16 ? 16 : U), 0, true>(g, tb.V, a.out, &s_src[wave][0], &s_dst[wave][0], &s_set[wave][0],
+                                                          &s_v1[wave][0], tb.sc, nf, &s_retry[wave][0]);
+                    }
                     wave_lds_fence();
                     bool again = false;
                     if (found) {
@@ -569,6 +559,7 @@ template <int W, int U, int WPB>
 __global__ void __launch_bounds__((WPB + 1) * kWave) query_dedup_kernel(const QueryArgs a) {
     constexpr int kTile = kWave * WPB;
     constexpr int kHash = 2 * kTile;
+    static_assert((kHash & (kHash - 1)) == 0, "the LDS table is probed with a mask: its size must be a power of two");
     constexpr uint32_t kNil = 0xFFFFFFFFu;
     constexpr uint64_t kMissed = ~0ull;
     __shared__ unsigned long long h_key[kHash];
@@ -1212,7 +1203,7 @@ uint64_t *counter_word(hps_cache *c, void *stream) {
 // the 106,496-key batch, 32 for 64 keys per wave).
 struct QueryShape { int kpw, u, wpb; };
 
-QueryShape query_shape(uint64_t n, bool coherent) {
+QueryShape query_shape(uint64_t n, bool coherent, bool dedup) {
     if (coherent) {
         // The checked variant reads rows 8 bytes per lane (one 512-byte row per wave load) and pays two
         // dependent round trips per group (rows, then the sequence words again), so a wave's rows
@@ -1220,22 +1211,34 @@ QueryShape query_shape(uint64_t n, bool coherent) {
         // work-group (2 per SIMD, 256 registers each) leave room for and 9 do not.  Measured in the
         // stand-alone test bed on the 106,496-key batch: groups of 16 rows, 9 waves 27.5 us; groups
         // of 32, 8 waves 23.1 us; one group, 8 waves 21.6 us.
+        // (1.7 M keys against a 64 GiB cache: 0.375 ms with this shape, 0.38-0.39 ms with groups of 16 or
+        // 32 rows and 5 waves, 0.49 ms with one group and 5 waves)
         if (n < (1u << 16)) return QueryShape{64, 64, 4};
-        if (n < (1u << 18)) return QueryShape{64, 64, 7};
-        return QueryShape{64, 64, 4};
+        return QueryShape{64, 64, 7};
     }
+    // Large batches run several work-groups per CU one after the other; measured (us per launch) for
+    // 425,984 / 1,703,936 keys of the hot cache, the 425,984-key streaming step and the 26-table launch:
+    //   4 waves, one group of 32   73.7 / 262.4 / 76.3 / 427
+    //   8 waves, one group of 26   70.2 / 288.0 / 68.4 / 418
+    //   7 waves, one group of 32   70.5 / 262.0 / 68.5 / 398
+    //   8 waves, groups of 16      71.7 / 255.0 / 70.3 / 386
     if (n < (1u << 16)) return QueryShape{64, 26, 4};
     if (n < (1u << 18)) return QueryShape{64, 26, 8};
-    return QueryShape{64, 32, 4};
+    if (n < (1u << 20) && !dedup) return QueryShape{64, 32, 7};   // (the in-tile dedup needs a power-of-two tile)
+    return QueryShape{64, 16, 8};
 }
 
 template <int W, int KPW, int U, int WPB>
 void launch_query_plain(const QueryArgs &a, bool dedup, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
-    if (dedup && KPW == kWave)
-        hipLaunchKernelGGL((query_dedup_kernel<W, (WPB == 8 ? 4 : 8), WPB>), dim3(grid), block, 0, st, a);
-    else if (a.g.d == 128) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, 128>), dim3(grid), block, 0, st, a);
+    if constexpr ((WPB & (WPB - 1)) == 0) {      // (the shapes chosen for dedup mode have 4 or 8 worker waves)
+        if (dedup && KPW == kWave) {
+            hipLaunchKernelGGL((query_dedup_kernel<W, (WPB == 8 ? 4 : 8), WPB>), dim3(grid), block, 0, st, a);
+            return;
+        }
+    }
+    if (a.g.d == 128) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, 128>), dim3(grid), block, 0, st, a);
     else   // any other row width: run-time row geometry needs more registers, so smaller groups under the 9-wave limit
         hipLaunchKernelGGL((query_kernel<W, KPW, (WPB == 8 ? 16 : U), WPB, false, 0>), dim3(grid), block, 0, st, a);
 }
@@ -1243,7 +1246,9 @@ void launch_query_plain(const QueryArgs &a, bool dedup, hipStream_t st) {
 template <int W, int KPW, int U, int WPB>
 void launch_query_checked(const QueryArgs &a, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
-    hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, true>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
+    if (a.g.d == 128) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, true, 128>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
+    else   // run-time row geometry: groups of 16 wave loads keep the kernel inside its registers
+        hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true, 0>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
 }
 
 template <int W>
@@ -1259,7 +1264,8 @@ hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, boo
         switch (id) {
             case 642604: launch_query_plain<W, 64, 26, 4>(a, dedup, st); break;
             case 642608: launch_query_plain<W, 64, 26, 8>(a, dedup, st); break;
-            case 643204: launch_query_plain<W, 64, 32, 4>(a, dedup, st); break;
+            case 643207: launch_query_plain<W, 64, 32, 7>(a, dedup, st); break;
+            case 641608: launch_query_plain<W, 64, 16, 8>(a, dedup, st); break;
             default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
         }
     }
@@ -1490,7 +1496,8 @@ static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, co
     a.n_dev = n_dev;
     bool coherent = false;                      // any table that may see concurrent writers makes the call careful
     for (uint32_t t = 0; t < n_tables; ++t) coherent = coherent || caches[t]->concurrent_writers.load() != 0;
-    const QueryShape shape = query_shape(total, coherent);
+    const bool dedup = !coherent && caches[0]->query_dedup.load() != 0;
+    const QueryShape shape = query_shape(total, coherent, dedup);
     // Keys per worker wave: at most 64, trimmed so that the work-groups come out as a whole number
     // of rounds over the CUs (106,496 keys in tiles of 8 x 52 are exactly 256 work-groups; tiles of
     // 8 x 64 would be 208, leaving 48 CUs idle).  Small batches go down to 16 keys per wave (8 below
@@ -1514,7 +1521,6 @@ static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, co
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
     a.g = make_geom(caches[0]->d);
-    const bool dedup = caches[0]->query_dedup.load() != 0;
     return launch_query(caches[0]->W, a, shape, coherent, dedup, static_cast<hipStream_t>(stream));
 }
 
