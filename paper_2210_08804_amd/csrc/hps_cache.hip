@@ -115,7 +115,7 @@ __device__ __forceinline__ void shared_release() { asm volatile("s_waitcnt vmcnt
 __device__ __forceinline__ uint64_t shared_ld64(const uint64_t *p) { return ld_agent(p); }
 __device__ __forceinline__ void shared_st64(uint64_t *p, uint64_t v) { st_agent(p, v); }
 
-struct Table {                 // one cache as the kernels see it
+struct alignas(64) Table {     // one cache as the kernels see it (one 64-byte line of the kernel arguments)
     int64_t  *K;
     float    *V;
     uint32_t *sc;              // [S][2]: {sequence word, victim counter} of a set
@@ -346,22 +346,31 @@ __device__ __forceinline__ int probe_wave(const int64_t *__restrict__ K, int64_t
 
 // ------------------------------------------------------------------ query
 
+// The scalars come first, in two 64-byte lines, then one line per table: a kernel's first reads of
+// its arguments miss in the scalar cache line by line.
 struct QueryArgs {
-    Table          tab[HPS_MAX_TABLES];
     const int64_t *keys;        // [T][B]
     float         *out;         // [T][B][d]
     uint32_t      *miss_idx;
     int64_t       *miss_keys;
     uint32_t      *n_miss;
     uint64_t      *slot;        // the stream's counter word: low 32 bits = misses so far, high 32 = tiles done
-    uint32_t       B;           // keys per table
     const uint32_t *n_dev;      // optional: the real batch length (<= B) is read on the device (one table only)
+    uint32_t       B;           // keys per table
     uint32_t       kpw;         // keys per worker wave (<= 64): lanes kpw..63 of a worker wave stay idle
     uint32_t       tiles_per_table;
     uint32_t       n_tiles;     // T * tiles_per_table (>= 1 even when B == 0)
     uint32_t       n_tables;    // T (<= HPS_MAX_TABLES <= 64: one helper lane per table finishes the call)
     RowGeom        g;
+    Table          tab[HPS_MAX_TABLES];
 };
+
+// Kernel arguments are read with scalar loads where they are first used, each followed by its own
+// wait; spread over several cache lines and basic blocks that put three to five dependent
+// scalar-cache misses in front of a wave's first key load (0.7 us of a 19 us query launch).  The
+// kernels therefore name everything a tile needs in ONE empty asm statement: all the loads are
+// issued together ahead of it and waited for once.
+#define HPS_ARGS_NOW(...) asm volatile("" ::__VA_ARGS__)
 
 // What the tile that finds every other tile of its call finished does (helper wave, all lanes):
 // publish the miss count, clear the call's counter word for the next call on the stream, and
@@ -393,7 +402,10 @@ __device__ __forceinline__ void finish_call(const QueryArgs &a, uint32_t n_miss,
 // (odd word), copies rows with copy_rows_checked and repeats for the keys whose set changed under
 // it.  A miss needs no check (an 8-byte key is read whole, and a key that stays cached is never
 // absent from its slot), so only hits are validated.
-template <int W, int KPW, int U, int WPB, bool kCoherent, int kD = 0>
+// kFull = true is launched for calls that name an LRU table or take their length from the device
+// (n_dev): only those kernels read g, stamp their hits and read *n_dev.  (As never-taken branches
+// in every kernel the three cost 0.4 us of a 19 us launch.)
+template <int W, int KPW, int U, int WPB, bool kCoherent, int kD = 0, bool kFull = false>
 __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArgs a) {
     __shared__ uint64_t s_src[WPB][KPW];
     __shared__ uint32_t s_dst[WPB][KPW];
@@ -407,6 +419,8 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x / kWave);
+    HPS_ARGS_NOW("s"(a.keys), "s"(a.out), "s"(a.n_dev), "s"(a.B), "s"(a.kpw), "s"(a.tiles_per_table), "s"(a.n_tiles),
+                 "s"(a.tab[0].K), "s"(a.tab[0].V), "s"(a.tab[0].T), "s"(a.tab[0].S), "s"(a.tab[0].smask));
     const RowGeom g = a.g;
     const bool many_tiles = a.n_tiles > gridDim.x;     // this work-group may take several tiles
 
@@ -423,15 +437,16 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
         const uint32_t lt = tile - t * a.tiles_per_table;
         if (wave < WPB) {
             const Table   &tb   = a.tab[t];
+            HPS_ARGS_NOW("s"(tb.K), "s"(tb.V), "s"(tb.T), "s"(tb.gdev), "s"(tb.S), "s"(tb.smask), "s"(tb.sc));
             // Alg. 2 "g <- g + 1": every tile of the call stamps with the count the call will leave
             // behind; the tile that finishes the call stores it (see the helper wave below).
-            const uint32_t g_call = tb.T ? *tb.gdev + 1u : 0u;
+            const uint32_t g_call = kFull && tb.T ? *tb.gdev + 1u : 0u;
             const uint32_t b    = (lt * WPB + wave) * a.kpw + lane;
             const bool     inb  = lane < (int)a.kpw && b < a.B;
             const uint32_t pos  = t * a.B + b;         // position in keys/out (< 2^32 checked on host)
 
             const int64_t key  = inb ? a.keys[pos] : kEmpty;      // keys[0 .. B) is readable also when n_dev says less
-            const bool    live = inb && (!a.n_dev || b < *a.n_dev);
+            const bool    live = inb && (!kFull || !a.n_dev || b < *a.n_dev);
             const bool    want = live && !is_reserved(key);
             const uint32_t set = want ? set_of(key, tb.S, tb.smask) : 0u;
             bool hit;
@@ -497,7 +512,7 @@ __global__ void __launch_bounds__((WPB + 1) * kWave) query_kernel(const QueryArg
             // Alg. 2: refresh the counter.  A plain store: the XCD's write-back L2 merges the many stores
             // a hot key draws (an agent-scope store per hit serialises them at the memory side and
             // triples the kernel time); they reach memory at the latest when the kernel ends.
-            if (tb.T && hit) tb.T[(uint64_t)set * W + (uint32_t)way] = g_call;
+            if (kFull && tb.T && hit) tb.T[(uint64_t)set * W + (uint32_t)way] = g_call;
 
             if (kCoherent) {
                 __syncthreads();                           // rows were copied inside the retry loop
@@ -1229,7 +1244,7 @@ QueryShape query_shape(uint64_t n, bool coherent, bool dedup) {
 }
 
 template <int W, int KPW, int U, int WPB>
-void launch_query_plain(const QueryArgs &a, bool dedup, hipStream_t st) {
+void launch_query_plain(const QueryArgs &a, bool dedup, bool full, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
     const dim3 block((WPB + 1) * kWave);
     if constexpr ((WPB & (WPB - 1)) == 0) {      // (the shapes chosen for dedup mode have 4 or 8 worker waves)
@@ -1238,34 +1253,46 @@ void launch_query_plain(const QueryArgs &a, bool dedup, hipStream_t st) {
             return;
         }
     }
-    if (a.g.d == 128) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, 128>), dim3(grid), block, 0, st, a);
-    else   // any other row width: run-time row geometry needs more registers, so smaller groups under the 9-wave limit
-        hipLaunchKernelGGL((query_kernel<W, KPW, (WPB == 8 ? 16 : U), WPB, false, 0>), dim3(grid), block, 0, st, a);
+    // any row width but 128: run-time row geometry needs more registers, so smaller groups under the 9-wave limit
+    constexpr int UG = WPB == 8 ? 16 : U;
+    if (a.g.d == 128) {
+        if (full) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, 128, true>), dim3(grid), block, 0, st, a);
+        else     hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, false, 128, false>), dim3(grid), block, 0, st, a);
+    } else {
+        if (full) hipLaunchKernelGGL((query_kernel<W, KPW, UG, WPB, false, 0, true>), dim3(grid), block, 0, st, a);
+        else     hipLaunchKernelGGL((query_kernel<W, KPW, UG, WPB, false, 0, false>), dim3(grid), block, 0, st, a);
+    }
 }
 
 template <int W, int KPW, int U, int WPB>
-void launch_query_checked(const QueryArgs &a, hipStream_t st) {
+void launch_query_checked(const QueryArgs &a, bool full, hipStream_t st) {
     const uint32_t grid = a.n_tiles < (1u << 20) ? a.n_tiles : (1u << 20);
-    if (a.g.d == 128) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, true, 128>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
-    else   // run-time row geometry: groups of 16 wave loads keep the kernel inside its registers
-        hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true, 0>), dim3(grid), dim3((WPB + 1) * kWave), 0, st, a);
+    const dim3 block((WPB + 1) * kWave);
+    // any row width but 128: run-time row geometry, groups of 16 wave loads keep the kernel inside its registers
+    if (a.g.d == 128) {
+        if (full) hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, true, 128, true>), dim3(grid), block, 0, st, a);
+        else     hipLaunchKernelGGL((query_kernel<W, KPW, U, WPB, true, 128, false>), dim3(grid), block, 0, st, a);
+    } else {
+        if (full) hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true, 0, true>), dim3(grid), block, 0, st, a);
+        else     hipLaunchKernelGGL((query_kernel<W, KPW, 16, WPB, true, 0, false>), dim3(grid), block, 0, st, a);
+    }
 }
 
 template <int W>
-hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, bool dedup, hipStream_t st) {
+hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, bool dedup, bool full, hipStream_t st) {
     const int id = q.kpw * 10000 + q.u * 100 + q.wpb;
     if (coherent) {
         switch (id) {
-            case 646404: launch_query_checked<W, 64, 64, 4>(a, st); break;
-            case 646407: launch_query_checked<W, 64, 64, 7>(a, st); break;
+            case 646404: launch_query_checked<W, 64, 64, 4>(a, full, st); break;
+            case 646407: launch_query_checked<W, 64, 64, 7>(a, full, st); break;
             default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
         }
     } else {
         switch (id) {
-            case 642604: launch_query_plain<W, 64, 26, 4>(a, dedup, st); break;
-            case 642608: launch_query_plain<W, 64, 26, 8>(a, dedup, st); break;
-            case 643207: launch_query_plain<W, 64, 32, 7>(a, dedup, st); break;
-            case 641608: launch_query_plain<W, 64, 16, 8>(a, dedup, st); break;
+            case 642604: launch_query_plain<W, 64, 26, 4>(a, dedup, full, st); break;
+            case 642608: launch_query_plain<W, 64, 26, 8>(a, dedup, full, st); break;
+            case 643207: launch_query_plain<W, 64, 32, 7>(a, dedup, full, st); break;
+            case 641608: launch_query_plain<W, 64, 16, 8>(a, dedup, full, st); break;
             default: return fail(HPS_ERR_INVALID_ARG, "query shape not compiled in");
         }
     }
@@ -1274,15 +1301,15 @@ hps_status_t launch_query_w(const QueryArgs &a, QueryShape q, bool coherent, boo
 }
 
 hps_status_t launch_query(uint32_t W, const QueryArgs &a, QueryShape q, bool coherent, bool dedup,
-                          hipStream_t st) {
+                          bool full, hipStream_t st) {
     switch (W) {
-        case 1:  return launch_query_w<1>(a, q, coherent, dedup, st);
-        case 2:  return launch_query_w<2>(a, q, coherent, dedup, st);
-        case 4:  return launch_query_w<4>(a, q, coherent, dedup, st);
-        case 8:  return launch_query_w<8>(a, q, coherent, dedup, st);
-        case 16: return launch_query_w<16>(a, q, coherent, dedup, st);
-        case 32: return launch_query_w<32>(a, q, coherent, dedup, st);
-        case 64: return launch_query_w<64>(a, q, coherent, dedup, st);
+        case 1:  return launch_query_w<1>(a, q, coherent, dedup, full, st);
+        case 2:  return launch_query_w<2>(a, q, coherent, dedup, full, st);
+        case 4:  return launch_query_w<4>(a, q, coherent, dedup, full, st);
+        case 8:  return launch_query_w<8>(a, q, coherent, dedup, full, st);
+        case 16: return launch_query_w<16>(a, q, coherent, dedup, full, st);
+        case 32: return launch_query_w<32>(a, q, coherent, dedup, full, st);
+        case 64: return launch_query_w<64>(a, q, coherent, dedup, full, st);
         default: return fail(HPS_ERR_INVALID_ARG, "unsupported ways");
     }
 }
@@ -1521,7 +1548,9 @@ static hps_status_t query_call(hps_cache_t *const *caches, uint32_t n_tables, co
     if (a.tiles_per_table == 0) a.tiles_per_table = 1;          // an empty batch still publishes n_miss = 0
     a.n_tiles = a.tiles_per_table * n_tables;
     a.g = make_geom(caches[0]->d);
-    return launch_query(caches[0]->W, a, shape, coherent, dedup, static_cast<hipStream_t>(stream));
+    bool full = n_dev != nullptr;               // a device-side length or any LRU table (Alg. 2 stamps) selects the full kernels
+    for (uint32_t t = 0; t < n_tables; ++t) full = full || a.tab[t].T != nullptr;
+    return launch_query(caches[0]->W, a, shape, coherent, dedup, full, static_cast<hipStream_t>(stream));
 }
 
 hps_status_t hps_cache_query_multi(hps_cache_t *const *caches, uint32_t n_tables, const int64_t *keys,
