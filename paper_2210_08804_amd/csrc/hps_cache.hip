@@ -110,8 +110,18 @@ template <typename T> __device__ __forceinline__ void st_agent(T *p, T v) {
 // vector memory operations have completed (s_waitcnt vmcnt(0)) between the steps: a wave's vector
 // memory instruction counter reaches zero only when every earlier load has returned its data and
 // every earlier store has been acknowledged by the level it was addressed to.
-__device__ __forceinline__ void shared_acquire() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-__device__ __forceinline__ void shared_release() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// The wait is the compiler's own s_waitcnt instruction (vmcnt(0), the other counters left alone:
+// 0x0F70 in the gfx9 encoding), not inline assembly: the pass that places the waits in front of
+// every use of a loaded register reads it and knows from there on that nothing is outstanding.
+// Behind an assembly string it assumed that every row load might still be in flight and put a
+// vmcnt(0) in front of each row store, so a wave had one store in flight at a time.
+__device__ __forceinline__ void wait_vm0() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void shared_acquire() { wait_vm0(); }
+__device__ __forceinline__ void shared_release() { wait_vm0(); }
 __device__ __forceinline__ uint64_t shared_ld64(const uint64_t *p) { return ld_agent(p); }
 __device__ __forceinline__ void shared_st64(uint64_t *p, uint64_t v) { st_agent(p, v); }
 
@@ -180,6 +190,11 @@ __device__ __forceinline__ void copy_rows(const RowGeom g, const float *__restri
                 ent[u] = e < cnt ? e : 0xFFFFFFFFu;
                 buf[u] = *reinterpret_cast<const f32x4 *>(src + (uint64_t)srcRow[e < cnt ? e : 0u] * d + off);
             }
+            // One wait for the whole group, stated where the compiler can see it.  The stores are
+            // predicated, so the compiler cannot count them among the outstanding operations and
+            // would make store k wait until at most U-1-k operations are in flight: the later
+            // stores of a group would wait for the earlier ones to be acknowledged.
+            __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0), other counters untouched
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (ent[u] != 0xFFFFFFFFu)
