@@ -1247,15 +1247,17 @@ QueryShape query_shape(uint64_t n, bool coherent, bool dedup) {
         return QueryShape{64, 64, 7};
     }
     // Large batches run several work-groups per CU one after the other; measured (us per launch) for
-    // 425,984 / 1,703,936 keys of the hot cache, the 425,984-key streaming step and the 26-table launch:
-    //   4 waves, one group of 32   73.7 / 262.4 / 76.3 / 427
-    //   8 waves, one group of 26   70.2 / 288.0 / 68.4 / 418
-    //   7 waves, one group of 32   70.5 / 262.0 / 68.5 / 398
-    //   8 waves, groups of 16      71.7 / 255.0 / 70.3 / 386
+    // 425,984 / 851,968 / 1,703,936 keys of the hot cache, the 425,984-key streaming step and the
+    // 26-table launch:
+    //   4 waves, one group of 32   76.6 / 141.2 / 275.4 / 77.6 / 439
+    //   8 waves, one group of 26   65.5 / 143.0 / 278.9 / 67.2 / 400
+    //   7 waves, one group of 32   65.3 / 125.7 / 244.0 / 65.4 / 378
+    //   8 waves, groups of 16      73.8 / 140.4 / 263.0 / 72.8 / 392
+    // (a second group waits, with its own loads, for the first group's stores: one group per wave)
     if (n < (1u << 16)) return QueryShape{64, 26, 4};
     if (n < (1u << 18)) return QueryShape{64, 26, 8};
-    if (n < (1u << 20) && !dedup) return QueryShape{64, 32, 7};   // (the in-tile dedup needs a power-of-two tile)
-    return QueryShape{64, 16, 8};
+    if (!dedup) return QueryShape{64, 32, 7};
+    return QueryShape{64, 16, 8};                  // (the in-tile dedup needs a power-of-two tile)
 }
 
 template <int W, int KPW, int U, int WPB>
