@@ -136,10 +136,10 @@ struct alignas(64) Table {     // one cache as the kernels see it (one 64-byte l
     uint32_t *flags;           // one word of HPS_FLAG_* bits raised by kernels
 };
 
-// Row geometry shared by all copy loops: a row is C = d/4 chunks of 16 bytes; LPR lanes
-// cooperate on one row (16 B per lane, contiguous, so a wave load covers 64/LPR whole rows).
 __device__ __forceinline__ uint32_t *seq_of(const Table &tb, uint32_t set) { return tb.sc + 2ull * set; }
 
+// Row geometry shared by all copy loops: a row is C = d/4 chunks of 16 bytes; LPR lanes
+// cooperate on one row (16 B per lane, contiguous, so a wave load covers 64/LPR whole rows).
 struct RowGeom {
     uint32_t d;                // fp32 per row
     uint32_t C;                // 16-byte chunks per row
@@ -152,8 +152,8 @@ struct RowGeom {
 
 // Copy `cnt` (> 0) rows listed in LDS: row srcRow[e] of `src` to row dstRow[e] of `dst`, for
 // e < cnt.  LPR lanes move one row, 16 B per lane, so a wave load/store covers 64/LPR whole
-// rows.  The rows go in groups of U wave loads, and a group's loads are ALL issued before its
-// first store (each store then waits only for its own load): with U = 26 the 52 rows of a wave
+// rows.  The rows go in groups of U wave loads: a group's loads are ALL issued, one wait for
+// them follows, then the group's stores go out back to back.  With U = 26 the 52 rows of a wave
 // of the 106,496-key batch (two 512-byte rows per wave load) are one group, every worker wave has
 // its whole share of the batch in flight at once, and the launch takes 18.4 us in the stand-alone
 // test bed against 21.5 us with two alternating buffers of 2 wave loads and 22.9 us with one
@@ -404,11 +404,12 @@ __device__ __forceinline__ void finish_call(const QueryArgs &a, uint32_t n_miss,
 // WPB*KPW positions; the first KPW lanes of each worker wave own one key each.
 //   workers  load key, hash, probe the set (probe_wave); misses are compacted per wave into LDS
 //            (ballot + mbcnt prefix), hits into the wave's <source slot, destination position>
-//            list; after one barrier the wave copies its rows (copy_rows).
-//   helper   after the barrier adds the tile's miss count to the call's counter word with one
-//            64-bit atomic (low half: misses so far, high half: tiles done), then writes the
-//            tile's miss entries from LDS to the global list.  The tile that finds every other
-//            tile done publishes *n_miss and clears the word for the next call.
+//            list; the wave then copies its rows (copy_rows) without waiting for the others.
+//   helper   once every worker wave has listed its misses (an LDS counter in the plain variant,
+//            a barrier in the checked one) it adds the tile's miss count to the call's counter
+//            word with one 64-bit atomic (low half: misses so far, high half: tiles done), then
+//            writes the tile's miss entries from LDS to the global list.  The tile that finds
+//            every other tile done publishes *n_miss and clears the word for the next call.
 // The helper exists so that no worker has the atomic's round trip in front of its row loads
 // (vector memory results return in issue order).
 //
