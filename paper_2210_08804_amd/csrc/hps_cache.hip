@@ -1255,7 +1255,9 @@ QueryShape query_shape(uint64_t n, bool coherent, bool dedup) {
     //   7 waves, one group of 32   65.3 / 125.7 / 244.0 / 65.4 / 378
     //   8 waves, groups of 16      73.8 / 140.4 / 263.0 / 72.8 / 392
     // (a second group waits, with its own loads, for the first group's stores: one group per wave)
-    if (n < (1u << 16)) return QueryShape{64, 26, 4};
+    // (4 against 8 workers, us per launch: 1,664 keys 5.6 / 6.1; 6,656 keys 6.9 / 7.3; 13,312 keys 8.3 / 8.3;
+    //  39,936 keys 12.5 / 11.6; 53,248 keys 14.3 / 12.8; 62,400 keys 16.8 / 13.5)
+    if (n < (1u << 14)) return QueryShape{64, 26, 4};
     if (n < (1u << 18)) return QueryShape{64, 26, 8};
     if (!dedup) return QueryShape{64, 32, 7};
     return QueryShape{64, 16, 8};                  // (the in-tile dedup needs a power-of-two tile)
