@@ -59,7 +59,7 @@ def parse():
     p.add_argument("--instances", type=int, default=1,
                    help="lookup: concurrent workers (threads), each with its own lookup object and stream, on one cache")
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-batches", type=int, default=100)
+    p.add_argument("--cpu-batches", type=int, default=1000)        # about 10 s of the oracle on one host core
     p.add_argument("--batched", type=int, default=4,
                    help="also time the same batches k per launch (0 or 1: skip)")
     p.add_argument("--no-checked", dest="also_checked", action="store_false",
