@@ -333,27 +333,31 @@ __device__ __forceinline__ int probe_wave(const int64_t *__restrict__ K, int64_t
                                           uint32_t set, bool want) {
     constexpr int G = kWave / W;                       // keys per wave load
     constexpr int R = (KPW + G - 1) / G;               // wave loads needed for KPW keys
+    constexpr int RC = R > 32 ? 32 : R;                // wave loads in flight together (64 for W = 64 would not fit the registers)
     const int lane = lane_id();
     const int slot = lane & (W - 1);
     const int sub  = lane / W;
-    int64_t sk[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int j = r * G + sub;
-        const uint32_t sj = (uint32_t)__shfl((int)set, j, kWave);   // 0 for lanes without a key: a valid set
-        const int64_t *p = K + (uint64_t)sj * W + slot;
-        sk[r] = kShared ? (int64_t)shared_ld64(reinterpret_cast<const uint64_t *>(p)) : *p;
-    }
     int way = -1;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int j = r * G + sub;
-        const int64_t kj = shfl64(key, j);
-        const int wj = __shfl((int)want, j, kWave);
-        const uint64_t m = __ballot(wj && sk[r] == kj);
-        if (lane / G == r) {
-            const uint64_t field = (W == 64) ? m : ((m >> ((lane % G) * W)) & ((1ull << (W & 63)) - 1));
-            if (field) way = __builtin_ctzll(field);
+    for (int r0 = 0; r0 < R; r0 += RC) {
+        int64_t sk[RC];
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
+            const int j = (r0 + r) * G + sub;
+            const uint32_t sj = (uint32_t)__shfl((int)set, j, kWave);   // 0 for lanes without a key: a valid set
+            const int64_t *p = K + (uint64_t)sj * W + slot;
+            sk[r] = kShared ? (int64_t)shared_ld64(reinterpret_cast<const uint64_t *>(p)) : *p;
+        }
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
+            const int j = (r0 + r) * G + sub;
+            const int64_t kj = shfl64(key, j);
+            const int wj = __shfl((int)want, j, kWave);
+            const uint64_t m = __ballot(wj && sk[r] == kj);
+            if (lane / G == r0 + r) {
+                const uint64_t field = (W == 64) ? m : ((m >> ((lane % G) * W)) & ((1ull << (W & 63)) - 1));
+                if (field) way = __builtin_ctzll(field);
+            }
         }
     }
     return way;
