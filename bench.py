@@ -1135,6 +1135,17 @@ def measure_ceiling(a, np, torch, B, h, host_keys, keys, mi, nm, outs, n, d, S, 
         B.hps_membench_gather(gv, d_slot[i % nb], n, d, outs[i % len(outs)])
         cnt[0] += 1
     us_gather = event_us(torch, one, a.steps, warm=20)
+    us_half = {}
+    if d == 128:                                 # the two halves of the same movement, each alone
+        for name, reads in (("reads_only", True), ("writes_only", False)):
+            cnt[0] = 0
+
+            def half_one(reads=reads):
+                i = cnt[0]
+                B.hps_membench_gather_half(gv, d_slot[i % nb], n, outs[i % len(outs)], reads)
+                cnt[0] += 1
+            us_half[name] = event_us(torch, half_one, a.steps, warm=20)
+        outs[0].view(torch.int32).fill_(0)       # (the write-only pass leaves its pattern in the out buffers)
     # a streaming copy that reads and writes as many bytes as the query's algorithmic figure
     half = int(alg_bytes // 2) // 4096 * 4096
     src = torch.empty(16 * half // 4, dtype=torch.float32, device="cuda")
@@ -1158,6 +1169,8 @@ def measure_ceiling(a, np, torch, B, h, host_keys, keys, mi, nm, outs, n, d, S, 
                      "precomputed; no hashing, probing or miss list), one launch per batch on the same stream and the same "
                      "rotating out buffers; output equal to the query's"),
             "gather_us_per_launch": round(us_gather, 3),
+            **({"gather_reads_only_us_per_launch": round(us_half["reads_only"], 3),
+                "gather_writes_only_us_per_launch": round(us_half["writes_only"], 3)} if us_half else {}),
             "streaming_copy_of_the_same_bytes_us_per_launch": round(us_copy, 3),
             "streaming_copy_1GiB_GBps_read_plus_write": round(2 * big / (us_big * 1e-6) / 1e9, 1),
         },

@@ -32,6 +32,15 @@ hps_status_t hps_membench_gather(const float *rows, const uint32_t *slot_of, siz
                                  float *out, void *stream);
 
 /*
+ * One half of that row movement at dim = 128 (512-byte rows), same work distribution and group
+ * size: reads != 0 loads the rows rows[slot_of[i]] and stores nothing; reads == 0 loads nothing and
+ * stores a register pattern to the rows out[i] of the same positions.  Their two times beside the
+ * time of both together show how far reads and writes share the memory system's time.
+ */
+hps_status_t hps_membench_gather_half(const float *rows, const uint32_t *slot_of, size_t n, float *out,
+                                      int reads, void *stream);
+
+/*
  * Streaming copy of `bytes` (a multiple of 16) from src to dst, 16 bytes per lane, several loads
  * in flight per lane; nontemporal != 0 marks loads and stores as streaming.
  */

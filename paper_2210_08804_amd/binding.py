@@ -35,7 +35,7 @@ EXPORTS = (
     "hps_dedup_noalloc",
     "hps_hostmap_create", "hps_hostmap_destroy", "hps_hostmap_put", "hps_hostmap_get", "hps_hostmap_fetch",
     "hps_hostmap_stats",
-    "hps_membench_gather", "hps_membench_copy",
+    "hps_membench_gather", "hps_membench_gather_half", "hps_membench_copy",
 )
 
 # lower-tier fetch callback of hps_lookup.h: (user, keys*, n, rows*)
@@ -93,6 +93,7 @@ def load_library():
         "hps_hostmap_get": [vp, vp, sz, vp, C.POINTER(sz)],
         "hps_hostmap_stats": [vp, C.POINTER(sz), C.POINTER(sz)],
         "hps_membench_gather": [vp, vp, sz, u32, vp, vp],
+        "hps_membench_gather_half": [vp, vp, sz, vp, C.c_int, vp],
         "hps_membench_copy": [vp, vp, sz, C.c_int, vp],
         "hps_cache_destroy": [vp],
         "hps_cache_query": [vp, vp, sz, vp, vp, vp, vp, vp],
@@ -263,6 +264,11 @@ def hps_backing_fetch(keys, n, dim, version=0, rows=None, n_dev=None, scatter_id
 def hps_membench_gather(rows, slot_of, n, dim, out, stream=None) -> None:
     _check(load_library().hps_membench_gather(_ptr(rows, torch.float32), _ptr(slot_of, torch.int32), n, dim,
                                               _ptr(out, torch.float32), _stream(stream)))
+
+
+def hps_membench_gather_half(rows, slot_of, n, out, reads, stream=None) -> None:
+    _check(load_library().hps_membench_gather_half(_ptr(rows, torch.float32), _ptr(slot_of, torch.int32), n,
+                                                   _ptr(out, torch.float32), 1 if reads else 0, _stream(stream)))
 
 
 def hps_membench_copy(src, dst, nbytes, nontemporal=True, stream=None) -> None:

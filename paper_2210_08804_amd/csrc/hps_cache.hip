@@ -1122,6 +1122,56 @@ __global__ void __launch_bounds__(WPB * kWave) membench_gather_kernel(const floa
     if (nh) copy_rows<U, kD>(g, rows, out, &s_src[wave][0], &s_dst[wave][0], nh);
 }
 
+// Half of that row movement: kReads = true issues the group's row loads and stores nothing (the
+// loaded words are folded into one value that is stored only if it equals a constant the data never
+// produces, so the loads stay); kReads = false stores a register pattern to the same destination
+// rows and loads nothing.  Work distribution, group size and access width are copy_rows'.
+template <int U, int WPB, bool kReads>
+__global__ void __launch_bounds__(WPB * kWave) membench_half_kernel(const float *__restrict__ rows,
+                                                                    const uint32_t *__restrict__ slot_of, uint32_t n,
+                                                                    uint32_t kpw, float *__restrict__ out) {
+    __shared__ uint32_t s_src[WPB][kWave];
+    __shared__ uint32_t s_dst[WPB][kWave];
+    const uint32_t lane = (uint32_t)lane_id();
+    const int wave = (int)(threadIdx.x / kWave);
+    const uint32_t pos = (blockIdx.x * WPB + wave) * kpw + lane;
+    const bool inb = lane < kpw && pos < n;
+    const uint32_t sl = inb ? slot_of[pos] : 0xFFFFFFFFu;
+    const bool hit = sl != 0xFFFFFFFFu;
+    const uint64_t hitmask = __ballot(hit);
+    const uint32_t cnt = (uint32_t)__popcll(hitmask);
+    if (hit) {
+        const int r = rank_in(hitmask);
+        s_src[wave][r] = sl;
+        s_dst[wave][r] = pos;
+    }
+    wave_lds_fence();
+    const uint32_t sub = lane >> 5, off = (lane & 31u) * 4u;            // 512-byte rows: 32 lanes per row, 2 rows per wave load
+    for (uint32_t e0 = 0; e0 < cnt; e0 += 2 * U) {
+        f32x4 buf[U];
+        uint32_t ent[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t e = e0 + 2 * u + sub;
+            ent[u] = e < cnt ? e : 0xFFFFFFFFu;
+            if (kReads) buf[u] = *reinterpret_cast<const f32x4 *>(rows + (uint64_t)s_src[wave][e < cnt ? e : 0u] * 128 + off);
+            else        buf[u] = f32x4{(float)lane, (float)u, (float)e, 1.0f};
+        }
+        if (kReads) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            f32x4 acc = buf[0];
+#pragma unroll
+            for (int u = 1; u < U; ++u) acc += buf[u];
+            if (acc.x == 1.2345678e-30f && acc.y == acc.x) out[0] = acc.z;     // never true for the backing rows
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ent[u] != 0xFFFFFFFFu)
+                    __builtin_nontemporal_store(buf[u], reinterpret_cast<f32x4 *>(out + (uint64_t)s_dst[wave][ent[u]] * 128 + off));
+        }
+    }
+}
+
 template <int U, bool kNT>
 __global__ void __launch_bounds__(kBlock) membench_copy_kernel(const f32x4 *__restrict__ src, f32x4 *__restrict__ dst, uint64_t n16) {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -1711,6 +1761,36 @@ hps_status_t hps_membench_gather(const float *rows, const uint32_t *slot_of, siz
     else
         hipLaunchKernelGGL((membench_gather_kernel<26, kWpb, 0>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0,
                            static_cast<hipStream_t>(stream), rows, slot_of, (uint32_t)n, (uint32_t)kpw, make_geom(dim), out);
+    HIP_TRY(hipGetLastError());
+    return HPS_OK;
+}
+
+hps_status_t hps_membench_gather_half(const float *rows, const uint32_t *slot_of, size_t n, float *out,
+                                      int reads, void *stream) {
+    if (n == 0) return HPS_OK;
+    if (!rows || !slot_of || !out) return fail(HPS_ERR_INVALID_ARG, "null pointer");
+    if (n >= (1ull << 32)) return fail(HPS_ERR_INVALID_ARG, "n must be < 2^32");
+    if (!aligned(rows, 16) || !aligned(out, 16)) return fail(HPS_ERR_INVALID_ARG, "rows and out must be 16-byte aligned");
+    int dev = 0, cus = 256;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus <= 0) cus = 256;
+    constexpr int kWpb = 8;                     // the shape hps_membench_gather uses
+    const uint64_t full = (uint64_t)kWpb * kWave * (uint64_t)cus;
+    const uint64_t rounds = (n + full - 1) / full;
+    uint64_t kpw = (n + kWpb * (uint64_t)cus * rounds - 1) / (kWpb * (uint64_t)cus * rounds);
+    if (kpw < 16) kpw = 16;
+    if (kpw > (uint64_t)kWave) kpw = kWave;
+    const uint64_t tile = kpw * kWpb;
+    const uint64_t blocks = (n + tile - 1) / tile;
+    if (blocks >= (1ull << 31)) return fail(HPS_ERR_INVALID_ARG, "n too large");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (reads)
+        hipLaunchKernelGGL((membench_half_kernel<26, kWpb, true>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0, st,
+                           rows, slot_of, (uint32_t)n, (uint32_t)kpw, out);
+    else
+        hipLaunchKernelGGL((membench_half_kernel<26, kWpb, false>), dim3((uint32_t)blocks), dim3(kWpb * kWave), 0, st,
+                           rows, slot_of, (uint32_t)n, (uint32_t)kpw, out);
     HIP_TRY(hipGetLastError());
     return HPS_OK;
 }
