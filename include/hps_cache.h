@@ -138,7 +138,7 @@ hps_status_t hps_cache_set_concurrent_writers(hps_cache_t *cache, int enabled);
  * (set_concurrent_writers(0)) elect one representative per distinct key of a 256- or 512-key
  * tile in LDS, probe and read each distinct row once and fan it out to the duplicate positions.
  * Results are identical.  Default 0: on MI355X the duplicate reads of a Zipf batch already hit
- * in L2, and the extra LDS rounds cost more than they save (measured 29 us vs 24 us per batch).
+ * in L2, and the extra LDS rounds cost more than they save (measured 29 us vs 18 us per batch).
  */
 hps_status_t hps_cache_set_query_dedup(hps_cache_t *cache, int enabled);
 
